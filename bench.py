@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Throughput of the logits path of the GRPO update on one MI355X.
+
+One step = one pass of the hot path over one synthetic micro-batch with inputs resident in
+HBM: group advantages -> softmax statistics (log-prob, entropy, log-partition) ->
+clipped loss + dlogits.  Default workload: the Qwen2.5-Math-1.5B-shaped micro-batch
+(2 queries x 8 rollouts x 1024 right-padded slots, V = 151936, bf16 logits).
+
+Prints one JSON line: tokens/s (valid token rows per second), the roofline of the dominant
+kernel measured with events on the launch stream, and the float64 CPU checker timed on a
+bounded sample of the same workload as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3"])
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gen-threads", type=int, default=16)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import aero_inputs as ai
+    import paper_2602_14338_amd as aero
+    from paper_2602_14338_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    name = args.workload
+    wl = ai.make_config("cfg2" if name == "cfg2-dense" else name)
+    if name == "cfg2-dense":   # same tensor shape, every slot a valid token
+        wl.lengths[:] = wl.T // wl.R
+        wl.token_rollout = np.repeat(np.arange(wl.R, dtype=np.int32), wl.T // wl.R)
+    T, V, ld, R, Q = wl.T, wl.V, wl.ld, wl.R, wl.Q
+    elt = 2 if wl.dtype == "bf16" else 4
+
+    # ---- inputs -> HBM (untimed) ------------------------------------------------------
+    t0 = time.time()
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    logits = torch.empty((T, ld), dtype=tdt, device=dev)
+    chunk = 2048
+    for r0 in range(0, T, chunk):
+        r1 = min(T, r0 + chunk)
+        h = wl.logits_rows(r0, r1, threads=args.gen_threads)
+        src = torch.from_numpy(h.view(np.int16)).view(torch.bfloat16) if wl.dtype == "bf16" else torch.from_numpy(h)
+        logits[r0:r1].copy_(src)
+    gen_s = time.time() - t0
+
+    def d(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+
+    rewards, lengths, offsets = d(wl.rewards), d(wl.lengths), d(wl.group_offsets)
+    keys = d(wl.keep_priority.view(np.int32))
+    targets, token_rollout = d(wl.targets), d(wl.token_rollout)
+    row_active = d((wl.token_rollout >= 0).astype(np.uint8))
+    params = aero.AdvParams(**wl.adv_params)
+
+    adv = torch.empty(R, device=dev)
+    weight = torch.empty(R, device=dev)
+    keep_mask = torch.empty(R, dtype=torch.uint8, device=dev)
+    kept_index = torch.empty(R, dtype=torch.int32, device=dev)
+    kept_offsets = torch.empty(Q + 1, dtype=torch.int32, device=dev)
+    zero_var = torch.empty(Q, dtype=torch.uint8, device=dev)
+    category = torch.empty(Q, dtype=torch.uint8, device=dev)
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    logprob = torch.empty(T, device=dev)
+    entropy = torch.empty(T, device=dev)
+    lse = torch.empty(T, device=dev)
+    loss = torch.empty(1, device=dev)
+    clip_frac = torch.empty(1, device=dev)
+    lp_out = torch.empty(T, device=dev)
+    dlogits = torch.empty_like(logits)
+    ws = torch.empty(aero.aero_workspace_bytes(binding.OP_GRPO_LOSS_BWD, T=T, V=V, R=R), dtype=torch.uint8, device=dev)
+
+    def step_adv():
+        aero.aero_group_advantage(rewards, lengths, offsets, keys, Q, R, params, adv, weight, keep_mask,
+                                  kept_index, kept_offsets, zero_var, category, err)
+
+    def step_fwd():
+        aero.aero_logprob_fwd(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err)
+
+    def step_bwd():
+        aero.aero_grpo_loss_bwd(logits, T, V, ld, targets, lse, old_logprob, token_rollout, adv, weight, R,
+                                wl.eps, wl.eps, 1.0, loss, clip_frac, lp_out, dlogits, ws, err)
+
+    # behaviour-policy log-probs: the current ones (from an untimed forward pass, as in
+    # training where they come from an earlier pass of the same kernel) plus seeded noise
+    step_adv()
+    step_fwd()
+    torch.cuda.synchronize()
+    old_logprob = d(ai.draw_old_logprob(logprob.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps))
+
+    for _ in range(args.warmup):
+        step_adv(); step_fwd(); step_bwd()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps --------------------------------------------------
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        ev[k][0].record(); step_adv()
+        ev[k][1].record(); step_fwd()
+        ev[k][2].record(); step_bwd()
+        ev[k][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_adv = float(np.mean([ev[k][0].elapsed_time(ev[k][1]) for k in range(K)]))
+    ms_fwd = float(np.mean([ev[k][1].elapsed_time(ev[k][2]) for k in range(K)]))
+    ms_bwd = float(np.mean([ev[k][2].elapsed_time(ev[k][3]) for k in range(K)]))
+    assert int(err.item()) == 0 and np.isfinite(loss.item())
+
+    # ---- algorithmic bytes per launch ----------------------------------------------------
+    n_valid = wl.n_valid
+    g_rows = int((lp_out != 0).sum().item())             # rows that carried signal
+    n_grad = int(round(g_rows * (1.0 - clip_frac.item())))   # unclipped rows: read + write
+    n_zero = T - n_grad                                  # write only
+    row_bytes = V * elt
+    fwd_bytes = n_valid * row_bytes
+    bwd_bytes = n_grad * 2 * row_bytes + n_zero * row_bytes
+    fwd_gbs = fwd_bytes / (ms_fwd * 1e-3) / 1e9
+    bwd_gbs = bwd_bytes / (ms_bwd * 1e-3) / 1e9
+    ms_step = wall / K * 1e3
+    out = {
+        "metric": "tokens/s, GRPO logprob+loss fwd/bwd at V=%d" % V,
+        "value": n_valid * K / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "T_rows": T, "valid_tokens": n_valid, "V": V, "storage": wl.dtype,
+                   "queries": Q, "rollouts": R, "signal_rows": g_rows, "grad_rows": n_grad,
+                   "zero_fill_rows": n_zero, "clip_eps": wl.eps, "input_gen_s": round(gen_s, 1)},
+        "kernels_ms": {"group_advantage": ms_adv, "logprob_fwd": ms_fwd, "grpo_loss_bwd": ms_bwd},
+        "roofline": {"kernel": "k_dlogits (timed as the whole aero_grpo_loss_bwd call)", "bound": "hbm",
+                     "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                     "traffic": None},
+        "roofline_fwd": {"kernel": "k_logprob_fwd", "bound": "hbm", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None},
+    }
+
+    # ---- CPU baseline: the float64 checker as it stands, on a bounded sample ---------------
+    if not args.no_cpu_baseline:
+        from oracle import aero_oracle as orc
+        # sample = the valid rows of evenly spaced 64-row generation blocks
+        B = ai.workloads.ROWS_PER_BLOCK
+        valid_mask = wl.token_rollout >= 0
+        blocks = [b for b in range((T + B - 1) // B) if valid_mask[b * B:(b + 1) * B].any()]
+        n = min(args.cpu_sample_rows, int(valid_mask.sum()))
+        stride = max(1, int(len(blocks) * B / max(n, 1)))
+        host_old = old_logprob.cpu().numpy()
+        tc = 0.0
+        t_ga = time.perf_counter()
+        ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority,
+                                 orc.AdvParams(**wl.adv_params))
+        tc += time.perf_counter() - t_ga
+        a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+        done = 0
+        for b in blocks[::stride]:
+            r0, r1 = b * B, min(T, (b + 1) * B)
+            sel = np.arange(r0, r1)[valid_mask[r0:r1]]
+            hz = wl.logits_rows(r0, r1)[valid_mask[r0:r1]]           # input generation: untimed
+            t1 = time.perf_counter()
+            orc.logprob_fwd(hz, wl.dtype, V, wl.targets[sel])
+            orc.grpo_loss_bwd(hz, wl.dtype, V, wl.targets[sel], host_old[sel], wl.token_rollout[sel], a32, w32,
+                              np.float32(wl.eps), np.float32(wl.eps), 1.0)
+            tc += time.perf_counter() - t1
+            done += len(sel)
+            if tc > 30.0 or done >= n:
+                break
+        out["cpu_baseline"] = {"value": done / tc, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d valid token rows of the same workload (every %d-th 64-row block), "
+                                         "all three steps, numpy float64 single thread" % (done, stride)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

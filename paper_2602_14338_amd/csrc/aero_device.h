@@ -1,0 +1,119 @@
+// Device-side helpers shared by the kernels: bf16 packing, wave64 reductions,
+// the running (max, sum-exp, sum-exp-times-logit) state of a softmax row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/aero.h"
+
+namespace aero {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kWave = 64;
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // one 16-byte global access
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+
+// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return *reinterpret_cast<uint32_t*>(&b);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float x) {
+  return uint16_t(pack_bf16x2(x, 0.f) & 0xffffu);
+}
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// Softmax row state relative to an offset m (any m close enough to the row maximum that
+// nothing overflows): s = sum exp(z - m), sz = sum exp(z - m) z.
+struct RowStat {
+  float m, s, sz;
+};
+
+__device__ __forceinline__ RowStat stat_identity() { return RowStat{-INFINITY, 0.f, 0.f}; }
+
+__device__ __forceinline__ RowStat stat_merge(RowStat a, RowStat b) {
+  float M = fmaxf(a.m, b.m);
+  float fa = (a.m == M) ? 1.f : exp2_fast((a.m - M) * kLog2e);
+  float fb = (b.m == M) ? 1.f : exp2_fast((b.m - M) * kLog2e);
+  return RowStat{M, a.s * fa + b.s * fb, a.sz * fa + b.sz * fb};
+}
+
+__device__ __forceinline__ RowStat stat_shfl_xor(RowStat a, int mask) {
+  return RowStat{__shfl_xor(a.m, mask, kWave), __shfl_xor(a.s, mask, kWave), __shfl_xor(a.sz, mask, kWave)};
+}
+
+__device__ __forceinline__ RowStat stat_wave_reduce(RowStat a) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) a = stat_merge(a, stat_shfl_xor(a, off));
+  return a;
+}
+
+// Workgroup-wide merge; every thread gets the result.  NT = threads per workgroup.
+template <int NT>
+__device__ __forceinline__ RowStat stat_block_reduce(RowStat a, RowStat* lds /*[NT/64]*/) {
+  a = stat_wave_reduce(a);
+  if constexpr (NT > kWave) {
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (lane == 0) lds[wave] = a;
+    __syncthreads();
+    RowStat r = lds[0];
+#pragma unroll
+    for (int w = 1; w < NT / kWave; ++w) r = stat_merge(r, lds[w]);
+    a = r;
+  }
+  return a;
+}
+
+// Fold N logits into a thread's running state.  The offset m is only moved when a value
+// exceeds it by more than kLazy nats, so the rescale is rare and exp(z - m) stays below
+// e^kLazy; sums of 2^24 such terms stay far inside fp32 range.
+constexpr float kLazy = 12.0f;
+
+template <int N>
+__device__ __forceinline__ void stat_update(RowStat& st, const float (&z)[N]) {
+  float vm = z[0];
+  if constexpr (N >= 3) {
+#pragma unroll
+    for (int k = 1; k + 1 < N; k += 2) vm = max3(vm, z[k], z[k + 1]);
+    if constexpr (N % 2 == 0) vm = fmaxf(vm, z[N - 1]);
+  } else if constexpr (N == 2) {
+    vm = fmaxf(vm, z[1]);
+  }
+  if (vm > st.m + kLazy) {   // also taken on first use (m = -inf)
+    float f = (st.m == -INFINITY) ? 0.f : exp2_fast((st.m - vm) * kLog2e);
+    st.s *= f;
+    st.sz *= f;
+    st.m = vm;
+  }
+  const float c = -st.m * kLog2e;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float e = exp2_fast(fmaf(z[k], kLog2e, c));
+    st.s += e;
+    st.sz = fmaf(e, z[k], st.sz);
+  }
+}
+
+__device__ __forceinline__ void unpack8(const u32x4_t& v, float (&z)[8]) {
+  z[0] = bf16_lo(v.x); z[1] = bf16_hi(v.x);
+  z[2] = bf16_lo(v.y); z[3] = bf16_hi(v.y);
+  z[4] = bf16_lo(v.z); z[5] = bf16_hi(v.z);
+  z[6] = bf16_lo(v.w); z[7] = bf16_hi(v.w);
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline aero_status launch_status() {
+  return hipGetLastError() == hipSuccess ? AERO_OK : AERO_ERR_HIP;
+}
+
+}  // namespace aero

@@ -1,0 +1,318 @@
+// Clipped-ratio surrogate (Eq. 2, beta = 0, loss = -J) and its gradient w.r.t. the logits
+// (App. A.1: grad rho = rho grad log pi; clipped tokens contribute nothing).
+//
+// Three steps on one stream:
+//   token terms  one thread per token: ratio, clip decision, loss term, g_t = dloss/dlogprob
+//   loss reduce  one workgroup, fixed summation order (bitwise reproducible), fp64 accumulator
+//   dlogits      one workgroup per row: dz = g_t (onehot - exp(z - lse)); rows with g_t == 0
+//                are not read, they are only filled with +0
+#include "aero_device.h"
+
+namespace aero {
+
+aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld,
+                               const int32_t* targets, const uint8_t* row_active, float* logprob,
+                               float* entropy, float* lse, int32_t* err_flag, hipStream_t s);
+
+// ---------------------------------------------------------------- workspace layout
+struct LossWorkspace {
+  float* g;          // [T] dloss / dlogprob
+  float* loss_term;  // [T]
+  int32_t* flag;     // [T] 0 = no signal, 1 = unclipped, 2 = clipped
+  float* lse;        // [T] used when the caller gives none
+  float* lp_tmp;     // [T] sink for the forward pass's log-prob when lse is recomputed
+  uint8_t* signal;   // [T] rows that carry signal, so the recomputing forward pass skips the rest
+};
+constexpr size_t kAlign = 256;
+inline size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
+size_t loss_workspace_bytes(int64_t T) { return 6 * seg(T); }
+inline LossWorkspace carve(void* ws, int64_t T) {
+  char* p = reinterpret_cast<char*>(ws);
+  const size_t s = seg(T);
+  return LossWorkspace{reinterpret_cast<float*>(p), reinterpret_cast<float*>(p + s),
+                       reinterpret_cast<int32_t*>(p + 2 * s), reinterpret_cast<float*>(p + 3 * s),
+                       reinterpret_cast<float*>(p + 4 * s), reinterpret_cast<uint8_t*>(p + 5 * s)};
+}
+
+// ---------------------------------------------------------------- which rows carry signal
+__global__ __launch_bounds__(256) void k_signal_mask(
+    int64_t T, int V, const int32_t* __restrict__ targets, const int32_t* __restrict__ token_rollout,
+    const float* __restrict__ adv, const float* __restrict__ weight, int R, uint8_t* __restrict__ signal) {
+  const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int i = token_rollout[t], y = targets[t];
+  signal[t] = (i >= 0 && i < R && y >= 0 && y < V && adv[i] != 0.f && weight[i] != 0.f) ? 1 : 0;
+}
+
+// ---------------------------------------------------------------- token terms
+// LP_GIVEN: the current log-prob is read from `logprob_in` (fused LM-head path) instead of
+// being formed as z[t, y] - lse[t].
+template <bool BF16, bool LP_GIVEN>
+__global__ __launch_bounds__(256) void k_token_terms(
+    const void* __restrict__ logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
+    const float* __restrict__ lse, const float* __restrict__ logprob_in,
+    const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
+    const float* __restrict__ adv, const float* __restrict__ weight, int R,
+    float eps_lo, float eps_hi, float grad_scale,
+    float* __restrict__ g_out, float* __restrict__ term_out, int32_t* __restrict__ flag_out,
+    float* __restrict__ logprob_out, int32_t* __restrict__ err_flag) {
+  const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int i = token_rollout[t];
+  const int y = targets[t];
+  float g = 0.f, term = 0.f, lp = 0.f;
+  int flag = 0;
+  if (i >= R || y >= V) {
+    if (err_flag) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
+  } else if (i >= 0 && y >= 0) {
+    const float A = adv[i], w = weight[i];
+    if (A != 0.f && w != 0.f) {   // decided before the ratio is touched
+      if constexpr (LP_GIVEN) {
+        lp = logprob_in[t];
+      } else {
+        float zy;
+        if constexpr (BF16) zy = bf16_to_f32(reinterpret_cast<const uint16_t*>(logits)[size_t(t) * size_t(ld) + y]);
+        else zy = reinterpret_cast<const float*>(logits)[size_t(t) * size_t(ld) + y];
+        lp = zy - lse[t];
+      }
+      const float rho = expf(lp - old_logprob[t]);
+      const float lo = 1.f - eps_lo, hi = 1.f + eps_hi;
+      const float clipped = fminf(fmaxf(rho, lo), hi);
+      const float s = fminf(rho * A, clipped * A);
+      const bool unclipped = A > 0.f ? (rho <= hi) : (rho >= lo);
+      term = -w * s;
+      g = unclipped ? -grad_scale * w * A * rho : 0.f;
+      flag = unclipped ? 1 : 2;
+    }
+  }
+  g_out[t] = g;
+  term_out[t] = term;
+  flag_out[t] = flag;
+  if (logprob_out) logprob_out[t] = lp;
+}
+
+// ---------------------------------------------------------------- loss reduce
+constexpr int kReduceNT = 1024;
+__global__ __launch_bounds__(kReduceNT) void k_loss_reduce(
+    const float* __restrict__ term, const int32_t* __restrict__ flag, int64_t T,
+    float* __restrict__ loss, float* __restrict__ clip_frac) {
+  __shared__ double s_sum[kReduceNT];
+  __shared__ int s_sig[kReduceNT], s_clip[kReduceNT];
+  double acc = 0.0;
+  int nsig = 0, nclip = 0;
+  for (int64_t t = threadIdx.x; t < T; t += kReduceNT) {   // fixed order per thread
+    acc += double(term[t]);
+    const int f = flag[t];
+    nsig += f != 0;
+    nclip += f == 2;
+  }
+  s_sum[threadIdx.x] = acc;
+  s_sig[threadIdx.x] = nsig;
+  s_clip[threadIdx.x] = nclip;
+  __syncthreads();
+  for (int off = kReduceNT / 2; off > 0; off >>= 1) {      // fixed tree
+    if (threadIdx.x < off) {
+      s_sum[threadIdx.x] += s_sum[threadIdx.x + off];
+      s_sig[threadIdx.x] += s_sig[threadIdx.x + off];
+      s_clip[threadIdx.x] += s_clip[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    loss[0] = float(s_sum[0]);
+    if (clip_frac) clip_frac[0] = s_sig[0] ? float(s_clip[0]) / float(s_sig[0]) : 0.f;
+  }
+}
+
+// ---------------------------------------------------------------- dlogits
+template <int NT, bool BF16, bool VEC>
+__global__ __launch_bounds__(NT) void k_dlogits(
+    const void* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
+    const float* __restrict__ lse, const float* __restrict__ g_arr, void* dlogits) {
+  const int64_t t = blockIdx.x;
+  const float g = g_arr[t];
+  constexpr size_t kEltBytes = BF16 ? 2 : 4;
+  constexpr int E = BF16 ? 8 : 4;
+  const size_t row_off = size_t(t) * size_t(ld) * kEltBytes;
+  const char* zrow = reinterpret_cast<const char*>(logits) + row_off;
+  char* drow = reinterpret_cast<char*>(dlogits) + row_off;
+  const int tid = threadIdx.x;
+
+  if (g == 0.f) {   // uniform over the workgroup: nothing to read
+    if constexpr (VEC) {
+      u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
+      const int nvec = V / E;
+      const u32x4_t zero = {0u, 0u, 0u, 0u};
+      for (int i = tid; i < nvec; i += NT) __builtin_nontemporal_store(zero, dv + i);
+      const int j = nvec * E + tid;
+      if (j < V) {
+        if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
+        else reinterpret_cast<float*>(drow)[j] = 0.f;
+      }
+    } else {
+      for (int j = tid; j < V; j += NT) {
+        if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
+        else reinterpret_cast<float*>(drow)[j] = 0.f;
+      }
+    }
+    return;
+  }
+
+  const int y = targets[t];
+  const float c = -lse[t] * kLog2e;
+  const float ng = -g;
+  // dz_j = -g * exp(z_j - lse) (+ g at the sampled token)
+  auto grad = [&](float z, int j) -> float {
+    float d = ng * exp2_fast(fmaf(z, kLog2e, c));
+    return j == y ? d + g : d;
+  };
+  if constexpr (VEC) {
+    const u32x4_t* zv = reinterpret_cast<const u32x4_t*>(zrow);
+    u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
+    const int nvec = V / E;
+    const int yvec = y / E;
+    constexpr int UNROLL = 4;
+    auto one = [&](const u32x4_t& v, int i) -> u32x4_t {
+      u32x4_t o;
+      if constexpr (BF16) {
+        float z[8];
+        unpack8(v, z);
+        float d[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) d[k] = ng * exp2_fast(fmaf(z[k], kLog2e, c));
+        if (i == yvec) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) d[k] += (k == (y & 7)) ? g : 0.f;
+        }
+        o.x = pack_bf16x2(d[0], d[1]);
+        o.y = pack_bf16x2(d[2], d[3]);
+        o.z = pack_bf16x2(d[4], d[5]);
+        o.w = pack_bf16x2(d[6], d[7]);
+      } else {
+        float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) d[k] = ng * exp2_fast(fmaf(d[k], kLog2e, c));
+        if (i == yvec) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) d[k] += (k == (y & 3)) ? g : 0.f;
+        }
+        o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
+        o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
+      }
+      return o;
+    };
+    int i = tid;
+    for (; i + (UNROLL - 1) * NT < nvec; i += UNROLL * NT) {
+      u32x4_t v[UNROLL];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(zv + i + u * NT);
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) __builtin_nontemporal_store(one(v[u], i + u * NT), dv + i + u * NT);
+    }
+    for (; i < nvec; i += NT) {
+      u32x4_t v = __builtin_nontemporal_load(zv + i);
+      __builtin_nontemporal_store(one(v, i), dv + i);
+    }
+    const int j = nvec * E + tid;
+    if (j < V) {
+      if constexpr (BF16) {
+        const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
+        reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(grad(z, j));
+      } else {
+        reinterpret_cast<float*>(drow)[j] = grad(reinterpret_cast<const float*>(zrow)[j], j);
+      }
+    }
+  } else {
+    for (int j = tid; j < V; j += NT) {
+      if constexpr (BF16) {
+        const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
+        reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(grad(z, j));
+      } else {
+        reinterpret_cast<float*>(drow)[j] = grad(reinterpret_cast<const float*>(zrow)[j], j);
+      }
+    }
+  }
+}
+
+template <bool BF16, bool VEC>
+static void dispatch_dlogits(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
+                             const float* lse, const float* g, void* dlogits, hipStream_t s) {
+  const int per_vec = VEC ? (BF16 ? 8 : 4) : 1;
+  const int64_t work = (V + per_vec - 1) / per_vec;
+  if (work <= 4 * 64)
+    hipLaunchKernelGGL((k_dlogits<64, BF16, VEC>), dim3((unsigned)T), dim3(64), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+  else if (work <= 16 * 256)
+    hipLaunchKernelGGL((k_dlogits<256, BF16, VEC>), dim3((unsigned)T), dim3(256), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+  else
+    hipLaunchKernelGGL((k_dlogits<512, BF16, VEC>), dim3((unsigned)T), dim3(512), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+}
+
+// Shared with the fused LM-head path: token terms from given log-probs, then the reduction.
+aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
+                                     const float* old_logprob, const int32_t* token_rollout,
+                                     const float* adv, const float* weight, int R, float eps_lo,
+                                     float eps_hi, float grad_scale, float* g, float* term,
+                                     int32_t* flag, float* loss, float* clip_frac, int32_t* err_flag,
+                                     hipStream_t s) {
+  const unsigned blocks = unsigned((T + 255) / 256);
+  hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
+                     targets, nullptr, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                     grad_scale, g, term, flag, nullptr, err_flag);
+  hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, term, flag, T, loss, clip_frac);
+  return launch_status();
+}
+
+}  // namespace aero
+
+extern "C" aero_status aero_grpo_loss_bwd(
+    const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
+    const float* lse, const float* old_logprob, const int32_t* token_rollout, const float* adv,
+    const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale, float* loss,
+    float* clip_frac, float* logprob_out, void* dlogits, int32_t* err_flag, void* workspace,
+    size_t workspace_bytes, void* stream) {
+  using namespace aero;
+  if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
+  if (dtype != AERO_BF16 && dtype != AERO_F32) return AERO_ERR_DTYPE;
+  if (!loss) return AERO_ERR_NULL;
+  hipStream_t s = as_stream(stream);
+  if (T > 0 && (!logits || !targets || !old_logprob || !token_rollout || !adv || !weight)) return AERO_ERR_NULL;
+  if (T > 0 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 ||
+                workspace_bytes < loss_workspace_bytes(T)))
+    return AERO_ERR_WORKSPACE;
+  LossWorkspace ws = carve(workspace, T);
+  if (T == 0) {
+    hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, nullptr, nullptr, T, loss, clip_frac);
+    return launch_status();
+  }
+  const unsigned blocks = unsigned((T + 255) / 256);
+  if (!lse) {
+    hipLaunchKernelGGL(k_signal_mask, dim3(blocks), dim3(256), 0, s, T, V, targets, token_rollout, adv, weight,
+                       R, ws.signal);
+    aero_status st = logprob_fwd_launch(logits, dtype, T, V, ld, targets, ws.signal, ws.lp_tmp, nullptr,
+                                        ws.lse, nullptr, s);
+    if (st != AERO_OK) return st;
+    lse = ws.lse;
+  }
+  if (dtype == AERO_BF16)
+    hipLaunchKernelGGL((k_token_terms<true, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
+                       lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
+                       ws.g, ws.loss_term, ws.flag, logprob_out, err_flag);
+  else
+    hipLaunchKernelGGL((k_token_terms<false, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
+                       lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
+                       ws.g, ws.loss_term, ws.flag, logprob_out, err_flag);
+  hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
+  if (dlogits) {
+    const size_t elt = dtype == AERO_BF16 ? 2 : 4;
+    const bool vec = reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0 &&
+                     (size_t(ld) * elt) % 16 == 0;
+    if (dtype == AERO_BF16) {
+      if (vec) dispatch_dlogits<true, true>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
+      else dispatch_dlogits<true, false>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
+    } else {
+      if (vec) dispatch_dlogits<false, true>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
+      else dispatch_dlogits<false, false>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
+    }
+  }
+  return launch_status();
+}

@@ -1,0 +1,85 @@
+"""Plumbing for the GPU parity tests: upload workloads, call the C ABI through the binding,
+bring results back as float64 / integer numpy arrays.  No arithmetic of the method here."""
+import numpy as np
+import torch
+
+import paper_2602_14338_amd as aero
+from paper_2602_14338_amd import binding
+
+DEV = "cuda:0"
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def logits_to_dev(arr, dtype):
+    """Host logits (float32 values or bf16 bit patterns in uint16) -> device tensor."""
+    if dtype == "bf16":
+        return torch.from_numpy(arr.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(arr).to(DEV)
+
+
+def to_np64(t):
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def run_group_advantage(wl_or_arrays, params: dict, keys="wl"):
+    if isinstance(wl_or_arrays, tuple):
+        rewards, lengths, offsets, kp = wl_or_arrays
+    else:
+        wl = wl_or_arrays
+        rewards, lengths, offsets, kp = wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority
+    if keys is None:
+        kp = None
+    Q, R = len(offsets) - 1, len(rewards)
+    d = dict(
+        adv=torch.full((R,), 7.0, device=DEV), weight=torch.full((R,), 7.0, device=DEV),
+        keep_mask=torch.full((R,), 9, dtype=torch.uint8, device=DEV),
+        kept_index=torch.full((R,), -5, dtype=torch.int32, device=DEV),
+        kept_offsets=torch.full((Q + 1,), -5, dtype=torch.int32, device=DEV),
+        zero_var=torch.full((Q,), 9, dtype=torch.uint8, device=DEV),
+        category=torch.full((Q,), 9, dtype=torch.uint8, device=DEV),
+        err=torch.zeros(1, dtype=torch.int32, device=DEV))
+    aero.aero_group_advantage(dev(rewards.astype(np.float32)), dev(lengths.astype(np.int32)),
+                              dev(offsets.astype(np.int32)),
+                              dev(kp.astype(np.uint32).view(np.int32)) if kp is not None else None,
+                              Q, R, aero.AdvParams(**params), d["adv"], d["weight"], d["keep_mask"],
+                              d["kept_index"], d["kept_offsets"], d["zero_var"], d["category"], d["err"])
+    torch.cuda.synchronize()
+    return d
+
+
+def run_fwd(logits_d, T, V, ld, targets, row_active=None, want_entropy=True):
+    lp = torch.full((T,), 7.0, device=DEV)
+    ent = torch.full((T,), 7.0, device=DEV) if want_entropy else None
+    lse = torch.full((T,), 7.0, device=DEV)
+    err = torch.zeros(1, dtype=torch.int32, device=DEV)
+    aero.aero_logprob_fwd(logits_d, T, V, ld, dev(targets), dev(row_active) if row_active is not None else None,
+                          lp, ent, lse, err)
+    torch.cuda.synchronize()
+    return lp, ent, lse, int(err.item())
+
+
+def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv, weight, eps=0.2,
+                 grad_scale=1.0, inplace=False, want_dlogits=True):
+    R = len(adv)
+    ws_bytes = aero.aero_workspace_bytes(binding.OP_GRPO_LOSS_BWD, T=T, V=V, R=R)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=DEV)
+    loss = torch.full((1,), 7.0, device=DEV)
+    clip = torch.full((1,), 7.0, device=DEV)
+    lp_out = torch.full((T,), 7.0, device=DEV)
+    if not want_dlogits:
+        dl = None
+    elif inplace:
+        dl = logits_d
+    else:
+        dl = torch.full_like(logits_d, 7.0)
+    err = torch.zeros(1, dtype=torch.int32, device=DEV)
+    aero.aero_grpo_loss_bwd(logits_d, T, V, ld, dev(targets), lse_d, dev(old_lp.astype(np.float32)),
+                            dev(token_rollout), dev(adv.astype(np.float32)), dev(weight.astype(np.float32)), R,
+                            eps, eps, grad_scale, loss, clip, lp_out, dl, ws, err)
+    torch.cuda.synchronize()
+    return dict(loss=loss, clip_frac=clip, logprob=lp_out, dlogits=dl, err=int(err.item()))

@@ -1,0 +1,305 @@
+"""GPU parity for the logits path: group advantages, softmax statistics, clipped loss and
+dlogits, each compared element by element with the float64 checker on the same seeded inputs.
+
+Tolerances (stated for the method): masks, kept indices and counts bit-exact; log-probs and
+entropy within 2e-3 absolute; loss within 1e-4 relative; dlogits within 1e-2 absolute and,
+because |dlogits| <= |g_t| is tiny, also scale-free: within 1e-2 |g_t| plus one bf16 / fp32
+rounding of the entry.  Advantages and weights within 1e-6 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import aero_inputs as ai
+from oracle import aero_oracle as orc
+from oracle.aero_oracle import AdvParams
+
+pytestmark = pytest.mark.gpu
+
+LP_TOL = 2e-3
+ENT_TOL = 2e-3
+LOSS_RTOL = 1e-4
+DZ_ATOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gh():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_helpers
+    return gpu_helpers
+
+
+# ------------------------------------------------------------------ group advantage
+
+MODES = [dict(), dict(reject_enable=1), dict(reject_enable=1, posterior_mode=1), dict(posterior_mode=1),
+         dict(reject_enable=1, k_ratio=2), dict(reject_enable=1, k_ratio=3, s_rescue=1, zero_keep=2,
+                                                posterior_mode=1, alpha0=0.5, beta0=2.0)]
+
+
+def check_groups(gh, arrays, params, keys="wl"):
+    rewards, lengths, offsets, kp = arrays
+    ref = orc.group_advantage(rewards, lengths, offsets, kp if keys else None, AdvParams(**params))
+    out = gh.run_group_advantage(arrays, params, keys=keys)
+    nk = int(ref["kept_offsets"][-1])
+    assert np.array_equal(out["keep_mask"].cpu().numpy(), ref["keep_mask"])
+    assert np.array_equal(out["kept_offsets"].cpu().numpy(), ref["kept_offsets"])
+    assert np.array_equal(out["kept_index"].cpu().numpy()[:nk], ref["kept_index"])
+    assert np.array_equal(out["zero_var"].cpu().numpy(), ref["zero_var"])
+    assert np.array_equal(out["category"].cpu().numpy(), ref["category"])
+    assert int(out["err"].item()) == ref["err"]
+    for k in ("adv", "weight"):
+        got = out[k].cpu().numpy().astype(np.float64)
+        assert np.allclose(got, ref[k], rtol=1e-6, atol=0), k
+        assert np.array_equal(got == 0, ref[k] == 0), k
+    return ref, out
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+@pytest.mark.parametrize("mode", range(len(MODES)))
+def test_group_advantage_configs(gh, name, mode):
+    wl = ai.make_config(name)
+    check_groups(gh, (wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority), MODES[mode])
+
+
+def test_group_advantage_edge_cases(gh):
+    rng = np.random.default_rng(21)
+    # big groups (several strides of 64), empty groups, single-rollout groups, tied keys, no keys
+    sizes = [0, 1, 200, 0, 65, 64, 2, 3, 129, 0]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(off[-1])
+    rewards = (rng.random(R) < 0.2).astype(np.float32)
+    rewards[off[5]:off[6]] = 1.0
+    lengths = rng.integers(0, 50, size=R).astype(np.int32)       # includes zero lengths
+    keys = rng.integers(0, 3, size=R).astype(np.uint32)
+    for params in MODES:
+        check_groups(gh, (rewards, lengths, off, keys), params)
+        check_groups(gh, (rewards, lengths, off, keys), params, keys=None)
+    # Q = 0 and R = 0
+    out = gh.run_group_advantage((np.zeros(0, np.float32), np.zeros(0, np.int32), np.array([0], np.int32), None),
+                                 dict(), keys=None)
+    assert out["kept_offsets"].cpu().tolist() == [0]
+    # many groups: the scan spans several entries per thread
+    sizes = rng.integers(0, 6, size=5000)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(off[-1])
+    rewards = (rng.random(R) < 0.4).astype(np.float32)
+    check_groups(gh, (rewards, rng.integers(1, 9, size=R).astype(np.int32), off,
+                      rng.integers(0, 2 ** 32, size=R, dtype=np.uint32)), dict(reject_enable=1, posterior_mode=1))
+
+
+def test_group_advantage_general_rewards_and_error_flag(gh):
+    rng = np.random.default_rng(22)
+    sizes = [5, 9, 16, 70]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rewards = rng.normal(size=int(off[-1])).astype(np.float32)
+    rewards[off[1]:off[2]] = 0.25                                    # all equal, non-binary
+    arrays = (rewards, np.full(len(rewards), 11, np.int32), off, None)
+    ref = orc.group_advantage(*arrays, AdvParams())
+    out = gh.run_group_advantage(arrays, dict(), keys=None)
+    assert np.allclose(out["adv"].cpu().numpy(), ref["adv"], rtol=2e-6, atol=1e-7)
+    assert out["zero_var"].cpu().tolist() == [0, 1, 0, 0] and int(out["err"].item()) == 0
+    out = gh.run_group_advantage(arrays, dict(reject_enable=1), keys=None)
+    assert int(out["err"].item()) & orc.ERR_NONBINARY_REWARD
+
+
+# ------------------------------------------------------------------ softmax statistics
+
+def check_fwd(gh, wl, row_active=None, targets=None, offset_elems=0):
+    targets = wl.targets if targets is None else targets
+    host = wl.logits_rows(0, wl.T)
+    ref = orc.logprob_fwd(host, wl.dtype, wl.V, targets, row_active)
+    if offset_elems:   # misaligned base pointer: slice a flat buffer
+        flat = np.concatenate([np.zeros(offset_elems, host.dtype), host.reshape(-1)])
+        d = gh.logits_to_dev(flat, wl.dtype)[offset_elems:]
+    else:
+        d = gh.logits_to_dev(host, wl.dtype)
+    lp, ent, lse, err = gh.run_fwd(d, wl.T, wl.V, wl.ld, targets, row_active)
+    ignored = targets < 0
+    if row_active is not None:
+        ignored |= row_active == 0
+    for got, want, tol in ((lp, ref[0], LP_TOL), (ent, ref[1], ENT_TOL), (lse, ref[2], LP_TOL)):
+        g = got.cpu().numpy().astype(np.float64)
+        assert np.isfinite(g).all()
+        assert np.abs(g - want).max() <= tol
+        assert not g[ignored].any()                 # ignored rows give exact zeros
+    return err
+
+
+def test_fwd_cfg1_full(gh):
+    assert check_fwd(gh, ai.make_config("cfg1")) == 0
+
+
+@pytest.mark.parametrize("V,ld", [(1000, 1000), (1000, 1008), (4999, 4999), (4999, 5008), (32768, 32768),
+                                  (151936, 151936), (152064, 152064), (7, 8), (1, 1), (65, 72)])
+def test_fwd_bf16_shapes(gh, V, ld):
+    slots = 4 if V > 100000 else 12
+    wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
+    active = (wl.token_rollout >= 0).astype(np.uint8)
+    assert check_fwd(gh, wl) == 0
+    assert check_fwd(gh, wl, row_active=active) == 0
+
+
+@pytest.mark.parametrize("V,ld", [(1024, 1024), (1023, 1023), (5000, 5004), (151936, 151936)])
+def test_fwd_f32_shapes(gh, V, ld):
+    wl = ai.make_config("cfg1", V=V, ld=ld, L=2)
+    assert check_fwd(gh, wl) == 0
+
+
+def test_fwd_misaligned_base_and_bad_targets(gh):
+    wl = ai.make_config("cfg2", V=4096, slots=6, len_lo=1, len_hi=6)
+    assert check_fwd(gh, wl, offset_elems=3) == 0
+    tg = wl.targets.copy()
+    tg[::5] = -1
+    assert check_fwd(gh, wl, targets=tg) == 0
+    tg[1] = wl.V          # outside the vocabulary: ignored row + error bit, no fault
+    tg[2] = 2 ** 31 - 1
+    host = wl.logits_rows(0, wl.T)
+    lp, ent, lse, err = gh.run_fwd(gh.logits_to_dev(host, "bf16"), wl.T, wl.V, wl.ld, tg)
+    assert err & 2 and lp[1].item() == 0 and lse[2].item() == 0
+    assert torch.isfinite(lp).all()
+
+
+def test_fwd_large_magnitudes(gh):
+    """Rows whose maximum moves a lot along the row and logits far outside exp's fp32 range."""
+    V = 20000
+    rng = np.random.default_rng(31)
+    z = rng.normal(0, 3, size=(6, V)).astype(np.float32)
+    z[0] += np.linspace(-300, 300, V, dtype=np.float32)       # maximum at the very end
+    z[1] += np.linspace(300, -300, V, dtype=np.float32)       # maximum at the start
+    z[2] *= 100.0
+    z[3] = 5.0                                                # uniform row
+    z[4, :] = -200.0
+    z[4, 77] = 200.0                                          # one dominant logit
+    z[5] -= 5000.0
+    tg = np.array([V - 1, 0, 5, 6, 77, 9], np.int32)
+    for dtype in ("f32", "bf16"):
+        host = z if dtype == "f32" else ai.f32_to_bf16_bits(z)
+        ref = orc.logprob_fwd(host, dtype, V, tg)
+        lp, ent, lse, err = gh.run_fwd(gh.logits_to_dev(host, dtype), 6, V, V, tg)
+        scale = np.maximum(1.0, np.abs(ref[2]))
+        assert (np.abs(lp.cpu().numpy() - ref[0]) <= LP_TOL * scale).all()
+        assert (np.abs(lse.cpu().numpy() - ref[2]) <= LP_TOL * scale).all()
+        assert (np.abs(ent.cpu().numpy() - ref[1]) <= ENT_TOL * scale).all()
+
+
+def test_fwd_empty(gh):
+    z = torch.zeros((0, 16), dtype=torch.bfloat16, device=gh.DEV)
+    gh.run_fwd(z, 0, 16, 16, np.zeros(0, np.int32))
+
+
+# ------------------------------------------------------------------ loss and dlogits
+
+def elt_rounding(dtype, ref_abs):
+    """One rounding of the stored gradient entry: bf16 has 8 significant bits, fp32 24."""
+    return ref_abs * (2.0 ** -8 if dtype == "bf16" else 2.0 ** -23) + 1e-30
+
+
+def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
+                   expect_clip=False):
+    host = wl.logits_rows(0, wl.T)
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
+    active = (wl.token_rollout >= 0).astype(np.uint8)
+    lp_ref, _, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets, active)
+    old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=sigma_old)
+    eps = np.float32(wl.eps)
+    ref = orc.grpo_loss_bwd(host, wl.dtype, wl.V, wl.targets, old, wl.token_rollout, ga["adv"].astype(np.float32),
+                            ga["weight"].astype(np.float32), eps, eps, grad_scale)
+    d = gh.logits_to_dev(host, wl.dtype)
+    lse_d = gh.dev(lse_ref.astype(np.float32)) if use_oracle_lse else None
+    out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, wl.token_rollout,
+                          ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace)
+    assert out["err"] == 0
+    loss = out["loss"].item()
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"]), (loss, ref["loss"])
+    assert abs(out["clip_frac"].item() - ref["clip_frac"]) < 1e-6
+    if expect_clip:
+        assert 0.02 < ref["clip_frac"] < 0.98
+    lp = out["logprob"].cpu().numpy().astype(np.float64)
+    assert np.abs(lp - ref["logprob"]).max() <= LP_TOL
+    dz = gh.to_np64(out["dlogits"])[:, :wl.V]
+    want = ref["dlogits"]
+    assert np.isfinite(dz).all()
+    assert np.abs(dz - want).max() <= DZ_ATOL
+    bound = 1e-2 * np.abs(ref["g"])[:, None] + elt_rounding(wl.dtype, np.abs(want))
+    assert (np.abs(dz - want) <= bound).all()
+    dead = ref["g"] == 0
+    raw = out["dlogits"][:, :wl.V]
+    bits = raw.view(torch.int16) if wl.dtype == "bf16" else raw.view(torch.int32)
+    assert not bits[torch.from_numpy(dead).to(gh.DEV)].any()       # exactly +0, sign bit included
+    if wl.ld > wl.V and not inplace:                                # pad columns are not written
+        assert (out["dlogits"][:, wl.V:].float() == 7.0).all()
+    return ref, out
+
+
+def test_loss_bwd_cfg1_full(gh):
+    wl = ai.make_config("cfg1")
+    ref, _ = check_loss_bwd(gh, wl, dict())
+    assert (ref["g"] == 0).sum() >= 2 * 8 * 64      # the two all-equal groups
+    check_loss_bwd(gh, wl, dict(), use_oracle_lse=False)
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, expect_clip=True)
+    check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, inplace=True, grad_scale=64.0)
+
+
+@pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10), (32768, 32768, 10)])
+def test_loss_bwd_cfg2_reduced(gh, V, ld, slots):
+    wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
+    check_loss_bwd(gh, wl, dict())
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, expect_clip=True)
+    check_loss_bwd(gh, wl, dict(), inplace=True)
+
+
+def test_loss_bwd_cfg3_reduced(gh):
+    wl = ai.make_config("cfg3", V=151936, T=320, Q=64, len_lo=1, len_hi=12)
+    ref, _ = check_loss_bwd(gh, wl, dict())
+    assert (ref["g"] == 0).any() and (ref["g"] != 0).any()
+    wl = ai.make_config("cfg3", V=8000, T=700, Q=64, len_lo=1, len_hi=12)
+    check_loss_bwd(gh, wl, dict(reject_enable=1), sigma_old=0.3, use_oracle_lse=False, expect_clip=True)
+    check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, expect_clip=True)
+
+
+def test_loss_is_run_to_run_identical_and_loss_only_mode(gh):
+    wl = ai.make_config("cfg3", V=8000, T=3000, Q=64, len_lo=1, len_hi=40)
+    host = wl.logits_rows(0, wl.T)
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, None, AdvParams())
+    lp_ref, _, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets)
+    old = ai.draw_old_logprob(lp_ref, 5, sigma=0.2)
+    d = gh.logits_to_dev(host, wl.dtype)
+    outs = [gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, None, old, wl.token_rollout, ga["adv"], ga["weight"],
+                            want_dlogits=(k < 2)) for k in range(3)]
+    assert outs[0]["loss"].view(torch.int32).item() == outs[1]["loss"].view(torch.int32).item()
+    assert outs[0]["loss"].view(torch.int32).item() == outs[2]["loss"].view(torch.int32).item()
+    assert torch.equal(outs[0]["dlogits"].view(torch.int16), outs[1]["dlogits"].view(torch.int16))
+
+
+def test_bad_rollout_index_and_empty_batch(gh):
+    wl = ai.make_config("cfg2", V=512, slots=4, len_lo=4, len_hi=4)
+    host = wl.logits_rows(0, wl.T)
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, None, AdvParams())
+    tr = wl.token_rollout.copy()
+    tr[3] = wl.R + 5
+    d = gh.logits_to_dev(host, wl.dtype)
+    out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, None, np.zeros(wl.T, np.float32) - 6.0, tr,
+                          ga["adv"], ga["weight"])
+    assert out["err"] & 4 and not out["dlogits"][3].float().any()
+    out = gh.run_loss_bwd(d[:0], 0, wl.V, wl.ld, np.zeros(0, np.int32), None, np.zeros(0, np.float32),
+                          np.zeros(0, np.int32), ga["adv"], ga["weight"])
+    assert out["loss"].item() == 0.0 and out["clip_frac"].item() == 0.0
+
+
+def test_host_side_argument_errors(gh):
+    import paper_2602_14338_amd as aero
+    z = torch.zeros((4, 16), dtype=torch.bfloat16, device=gh.DEV)
+    t = torch.zeros(4, dtype=torch.int32, device=gh.DEV)
+    f = torch.zeros(4, device=gh.DEV)
+    with pytest.raises(aero.AeroError, match="leading dimension"):
+        aero.aero_logprob_fwd(z, 4, 16, 8, t, None, f, f, f)
+    with pytest.raises(aero.AeroError, match="leading dimension"):
+        aero.aero_logprob_fwd(z, 4, 0, 16, t, None, f, f, f)
+    with pytest.raises(aero.AeroError, match="NULL"):
+        aero.aero_logprob_fwd(z, 4, 16, 16, None, None, f, f, f)
+    with pytest.raises(aero.AeroError, match="unsupported dtype"):
+        aero.aero_logprob_fwd(z.to(torch.float16), 4, 16, 16, t, None, f, f, f)
+    with pytest.raises(aero.AeroError, match="workspace"):
+        aero.aero_grpo_loss_bwd(z, 4, 16, 16, t, None, f, t, f, f, 4, 0.2, 0.2, 1.0, f[:1], None, None, None,
+                                torch.zeros(8, dtype=torch.uint8, device=gh.DEV))
