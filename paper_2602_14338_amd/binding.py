@@ -66,9 +66,8 @@ def _load() -> C.CDLL:
     lib.aero_grpo_loss_bwd.restype = i32
     lib.aero_grpo_loss_bwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, i32, f32, f32, f32,
                                        p, p, p, p, p, p, sz, p]
-    if hasattr(lib, "aero_lmhead_logprob_fused"):
-      lib.aero_lmhead_logprob_fused.restype = i32
-      lib.aero_lmhead_logprob_fused.argtypes = [p, p, i64, i32, i32, p, p, p, p, p, p, p, p, i32, f32, f32, f32,
+    lib.aero_lmhead_logprob_fused.restype = i32
+    lib.aero_lmhead_logprob_fused.argtypes = [p, p, i64, i32, i32, p, p, p, p, p, p, p, p, i32, f32, f32, f32,
                                               p, p, p, p, i32, p, p, sz, p]
     return lib
 

@@ -255,9 +255,10 @@ aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, c
                                      int32_t* flag, float* loss, float* clip_frac, int32_t* err_flag,
                                      hipStream_t s) {
   const unsigned blocks = unsigned((T + 255) / 256);
-  hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
-                     targets, nullptr, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                     grad_scale, g, term, flag, nullptr, err_flag);
+  if (T > 0)
+    hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
+                       targets, nullptr, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                       grad_scale, g, term, flag, nullptr, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, term, flag, T, loss, clip_frac);
   return launch_status();
 }

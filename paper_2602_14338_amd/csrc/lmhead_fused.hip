@@ -1,5 +1,495 @@
-// LM head fused into the softmax statistics and the loss gradients (work in progress).
-#include "aero_device.h"
+// LM head fused into the softmax statistics, the clipped loss and its gradients: logits
+// z = hidden @ weight^T exist only as fp32 MFMA accumulator tiles.
+//
+// Forward   k_fused_stats   tile of z^T (vocab rows x token columns): every lane owns one
+//                           token column per block, so the running (offset, sum exp,
+//                           sum exp*z) is a per-lane register recurrence with no shuffles
+//           k_fused_combine merges the per-tile partials of a token, adds the sampled
+//                           token's logit (one H-long dot product) -> logprob, entropy, lse
+// Backward  token terms + loss reduce (shared with the logits path), then
+//           k_compact_tokens  tokens with g_t != 0 are gathered (that is exactly the set AERO's
+//                             curation leaves), hidden is gathered / transposed once, weight
+//                             is transposed once, and per vocabulary chunk:
+//           k_fused_dz        recompute the z^T tile, dz = g (onehot - exp(z - lse)) -> bf16,
+//                             stored both as [token, vocab] and [vocab, token]
+//           k_gemm_dh         dhidden_acc += dz_chunk @ weight_chunk        (fp32, per chunk)
+//           k_gemm_dw         dweight[chunk rows] = dz_chunk^T @ hidden     (complete per chunk)
+//           k_scatter_dh      fp32 accumulator rows -> bf16 dhidden at the original token rows
+// All contractions use the same 256 x 256 x 64 MFMA tile with both operands K-contiguous.
+#include "gemm_tile.h"
+
 namespace aero {
-size_t fused_workspace_bytes(int64_t T, int32_t V, int32_t H) { return 0; }
+
+aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
+                                     const float* old_logprob, const int32_t* token_rollout,
+                                     const float* adv, const float* weight, int R, float eps_lo,
+                                     float eps_hi, float grad_scale, float* g, float* term,
+                                     int32_t* flag, float* loss, float* clip_frac, int32_t* err_flag,
+                                     hipStream_t s);
+
+constexpr size_t kWsAlign = 256;
+inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------------------------
+// workspace
+// ------------------------------------------------------------------------------------------
+struct FusedPlan {
+  int64_t T, T_pad;
+  int V, V_ld, H, tiles_v, VC;   // VC: vocabulary chunk of the backward pass
+  size_t off_part, off_g, off_term, off_flag, off_idx, off_pos, off_nact, off_gc, off_lsec, off_yc,
+      off_hc, off_hTc, off_WT, off_dz, off_dzT, off_dhacc, total;
+};
+
+static FusedPlan make_plan(int64_t T, int V, int H) {
+  FusedPlan p{};
+  p.T = T;
+  p.T_pad = int64_t(up(size_t(T > 0 ? T : 1), kTile));
+  p.V = V;
+  p.V_ld = int(up(size_t(V), kTile));
+  p.H = H;
+  p.tiles_v = p.V_ld / kTile;
+  // chunk so that dz and its transpose (2 x T_pad x VC bf16) stay around 256 MiB in total
+  int64_t vc = (int64_t(64) << 20) / p.T_pad / kTile * kTile;
+  if (vc < kTile) vc = kTile;
+  if (vc > p.V_ld) vc = p.V_ld;
+  p.VC = int(vc);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up(bytes, kWsAlign); return at; };
+  p.off_part = take(size_t(3) * p.tiles_v * p.T_pad * 4);
+  p.off_g = take(size_t(p.T_pad) * 4);
+  p.off_term = take(size_t(p.T_pad) * 4);
+  p.off_flag = take(size_t(p.T_pad) * 4);
+  p.off_idx = take(size_t(p.T_pad) * 4);
+  p.off_pos = take(size_t(p.T_pad) * 4);
+  p.off_nact = take(16);
+  p.off_gc = take(size_t(p.T_pad) * 4);
+  p.off_lsec = take(size_t(p.T_pad) * 4);
+  p.off_yc = take(size_t(p.T_pad) * 4);
+  p.off_hc = take(size_t(p.T_pad) * H * 2);
+  p.off_hTc = take(size_t(H) * p.T_pad * 2);
+  p.off_WT = take(size_t(H) * p.V_ld * 2);
+  p.off_dz = take(size_t(p.T_pad) * p.VC * 2);
+  p.off_dzT = take(size_t(p.VC) * p.T_pad * 2);
+  p.off_dhacc = take(size_t(p.T_pad) * H * 4);
+  p.total = o;
+  return p;
+}
+
+size_t fused_workspace_bytes(int64_t T, int32_t V, int32_t H) {
+  if (T < 0 || V < 1 || H < 1) return 0;
+  return make_plan(T, V, H).total;
+}
+
+// ------------------------------------------------------------------------------------------
+// forward: per-tile softmax partials
+// ------------------------------------------------------------------------------------------
+// grid: tiles_v * tiles_t workgroups.  part_* are [tiles_v][T_pad].
+__global__ __launch_bounds__(kGemmNT, 1) void k_fused_stats(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hd, int V, int64_t T, int H,
+    int tiles_v, int tiles_t, int64_t T_pad, float* __restrict__ part_m, float* __restrict__ part_s,
+    float* __restrict__ part_sz) {
+  extern __shared__ __align__(16) uint16_t smem[];
+  int tv, tt;
+  tile_of_block(tiles_v, tiles_t, tv, tt);
+  const int m0 = tv * kTile, n0 = tt * kTile;
+  f32x16_t acc[4][4];
+  gemm_tile(W, H, V, Hd, H, int(T), H, m0, n0, smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const bool full = m0 + kTile <= V;
+  RowStat st[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    st[nb] = stat_identity();
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      if (full) {
+        float z[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) z[i] = acc[mb][nb][i];
+        stat_update<16>(st[nb], z);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (m0 + acc_row(wm, mb, i, lane) < V) {
+            float z[1] = {acc[mb][nb][i]};
+            stat_update<1>(st[nb], z);
+          }
+      }
+    }
+    st[nb] = stat_merge(st[nb], stat_shfl_xor(st[nb], 32));   // the two row-halves of the block
+  }
+  // the two waves that share these token columns (wm = 0, 1) merge through LDS
+  RowStat* xch = reinterpret_cast<RowStat*>(smem);   // [2 (wn)][128]
+  if (wm == 1 && lane < 32) {
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) xch[wn * 128 + nb * 32 + lane] = st[nb];
+  }
+  __syncthreads();
+  if (wm == 0 && lane < 32) {
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const RowStat r = stat_merge(st[nb], xch[wn * 128 + nb * 32 + lane]);
+      const int64_t t = n0 + wn * 128 + nb * 32 + lane;   // < T_pad
+      const int64_t o = int64_t(tv) * T_pad + t;
+      part_m[o] = r.m;
+      part_s[o] = r.s;
+      part_sz[o] = r.sz;
+    }
+  }
+}
+
+// One wave per token: merge the tiles_v partials, compute the sampled token's logit.
+__global__ __launch_bounds__(256) void k_fused_combine(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hd, int V, int64_t T, int H, int tiles_v,
+    int64_t T_pad, const float* __restrict__ part_m, const float* __restrict__ part_s,
+    const float* __restrict__ part_sz, const int32_t* __restrict__ targets, float* __restrict__ logprob,
+    float* __restrict__ entropy, float* __restrict__ lse_out, int32_t* __restrict__ err_flag) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const int y = targets[t];
+  if (y < 0 || y >= V) {   // ignored row
+    if (lane == 0) {
+      logprob[t] = 0.f;
+      lse_out[t] = 0.f;
+      if (entropy) entropy[t] = 0.f;
+      if (y >= V && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
+    }
+    return;
+  }
+  RowStat st = stat_identity();
+  for (int tv = lane; tv < tiles_v; tv += kWave) {
+    const int64_t o = int64_t(tv) * T_pad + t;
+    st = stat_merge(st, RowStat{part_m[o], part_s[o], part_sz[o]});
+  }
+  st = stat_wave_reduce(st);
+  float dot = 0.f;
+  const uint16_t* hr = Hd + t * H;
+  const uint16_t* wr = W + int64_t(y) * H;
+  for (int k = lane; k < H; k += kWave) dot = fmaf(bf16_to_f32(hr[k]), bf16_to_f32(wr[k]), dot);
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+  if (lane == 0) {
+    const float lse = st.m + logf(st.s);
+    logprob[t] = dot - lse;
+    lse_out[t] = lse;
+    if (entropy) entropy[t] = lse - st.sz / st.s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: compaction, transposes
+// ------------------------------------------------------------------------------------------
+// Single workgroup, order-preserving: idx[j] = j-th token with g != 0, pos[t] = j or -1,
+// nact[0] = count, nact[1] = count rounded up to a tile.  Compacted per-token scalars follow.
+__global__ __launch_bounds__(1024) void k_compact_tokens(
+    const float* __restrict__ g, const float* __restrict__ lse, const int32_t* __restrict__ targets, int64_t T,
+    int64_t T_pad, int32_t* __restrict__ idx, int32_t* __restrict__ pos, int32_t* __restrict__ nact,
+    float* __restrict__ gc, float* __restrict__ lsec, int32_t* __restrict__ yc) {
+  __shared__ int part[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (T + 1023) / 1024;
+  const int64_t lo = min(T, tid * per), hi = min(T, lo + per);
+  int cnt = 0;
+  for (int64_t t = lo; t < hi; ++t) cnt += g[t] != 0.f;
+  part[tid] = cnt;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = tid ? part[tid - 1] : 0;
+  const int total = part[1023];
+  for (int64_t t = lo; t < hi; ++t) {
+    if (g[t] != 0.f) {
+      idx[run] = int(t);
+      pos[t] = run;
+      gc[run] = g[t];
+      lsec[run] = lse[t];
+      yc[run] = targets[t];
+      ++run;
+    } else {
+      pos[t] = -1;
+    }
+  }
+  for (int64_t j = total + tid; j < T_pad; j += 1024) {   // padding entries: no gradient
+    idx[j] = -1;
+    gc[j] = 0.f;
+    lsec[j] = 0.f;
+    yc[j] = -1;
+  }
+  if (tid == 0) {
+    nact[0] = total;
+    nact[1] = (total + kTile - 1) / kTile * kTile;
+  }
+}
+
+// out[c][r] = in[src(r)][c] for r < n_out_rows (src = idx[r] if idx else r; src < 0 or
+// r >= rows_in_valid -> 0), c < C.  Also writes the gathered copy gath[r][c] when gath != null.
+// 64 x 64 tiles through LDS.  grid: (ceil(n_out_rows/64), ceil(C_out/64)); columns C..C_out of
+// `in` do not exist and are written as zero rows of `out`.
+__global__ __launch_bounds__(256) void k_gather_transpose(
+    const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows_in_valid, int C, const int32_t* __restrict__ idx,
+    int64_t n_out_rows, uint16_t* __restrict__ out, int64_t ld_out, uint16_t* __restrict__ gath, int64_t ld_gath) {
+  __shared__ uint16_t tile[64][66];
+  const int64_t r0 = int64_t(blockIdx.x) * 64;
+  const int c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int64_t r = r0 + rr;
+    const int c = c0 + tx;
+    uint16_t v = 0;
+    if (r < n_out_rows && c < C) {
+      const int64_t src = idx ? int64_t(idx[r]) : r;
+      if (src >= 0 && src < rows_in_valid) v = in[src * ld_in + c];
+      if (gath) gath[r * ld_gath + c] = v;
+    }
+    tile[rr][tx] = v;
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int64_t r = r0 + tx;
+    const int c = c0 + cc;
+    if (r < n_out_rows && c < C) out[int64_t(c) * ld_out + r] = tile[tx][cc];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: dz tiles for one vocabulary chunk
+// ------------------------------------------------------------------------------------------
+// z^T tile rows = vocab [v0 + m0, ...), columns = compacted tokens.  dz[t][v - v0] and
+// dzT[v - v0][t] in bf16; entries outside the vocabulary or the active tokens are zero.
+__global__ __launch_bounds__(kGemmNT, 1) void k_fused_dz(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hc, int V, int H, int v0, int vc,
+    int tiles_v, int tiles_t, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
+    const float* __restrict__ gc, const float* __restrict__ lsec, const int32_t* __restrict__ yc,
+    uint16_t* __restrict__ dz, uint16_t* __restrict__ dzT) {
+  extern __shared__ __align__(16) uint16_t smem[];
+  int tv, tt;
+  tile_of_block(tiles_v, tiles_t, tv, tt);
+  const int m0 = tv * kTile, n0 = tt * kTile;
+  if (n0 >= nact[1]) return;   // beyond the active tokens: uniform exit
+  f32x16_t acc[4][4];
+  gemm_tile(W + int64_t(v0) * H, H, vc, Hc, H, int(T_pad), H, m0, n0, smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    const int64_t t = n0 + acc_col(wn, nb, lane);
+    const float g = gc[t], ng = -g;
+    const float c = -lsec[t] * kLog2e;
+    const int yrel = yc[t] - v0;   // row of the sampled token inside this chunk, if any
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float d[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int row = m0 + acc_row(wm, mb, i4 * 4 + j, lane);
+          float v = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
+          if (row == yrel) v += g;
+          d[j] = row < vc ? v : 0.f;
+        }
+        const int row0 = m0 + acc_row(wm, mb, i4 * 4, lane);   // 4 consecutive vocab rows
+        const uint32_t lo = pack_bf16x2(d[0], d[1]), hi = pack_bf16x2(d[2], d[3]);
+        uint2 pk = {lo, hi};
+        *reinterpret_cast<uint2*>(dz + t * VC + row0) = pk;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          dzT[int64_t(row0 + j) * T_pad + t] = uint16_t((j < 2 ? lo : hi) >> ((j & 1) * 16));
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: the two gradient GEMMs
+// ------------------------------------------------------------------------------------------
+// dh_acc[t][h] (+)= sum_k dz[t][k] WT[h][v0 + k]     M = active tokens, N = H, K = vc
+__global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dh(
+    const uint16_t* __restrict__ dz, int VC, const uint16_t* __restrict__ WT, int64_t V_ld, int v0, int vc8,
+    int H, int tiles_t, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, int accumulate,
+    float* __restrict__ dh_acc) {
+  extern __shared__ __align__(16) uint16_t smem[];
+  int tt, th;
+  tile_of_block(tiles_t, tiles_h, tt, th);
+  const int m0 = tt * kTile, n0 = th * kTile;
+  if (m0 >= nact[1]) return;
+  f32x16_t acc[4][4];
+  gemm_tile(dz, VC, int(T_pad), WT + v0, V_ld, H, vc8, m0, n0, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    const int col = n0 + acc_col(wn, nb, lane);
+    if (col >= H) continue;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float* p = dh_acc + int64_t(m0 + acc_row(wm, mb, i, lane)) * H + col;
+        *p = accumulate ? *p + acc[mb][nb][i] : acc[mb][nb][i];
+      }
+  }
+}
+
+// dW[v0 + m][h] = sum_t dzT[m][t] hTc[h][t]          M = vc, N = H, K = active tokens (padded)
+template <bool OUT_BF16>
+__global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dw(
+    const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int64_t T_pad, int v0, int vc, int H,
+    int tiles_v, int tiles_h, const int32_t* __restrict__ nact, void* __restrict__ dW) {
+  extern __shared__ __align__(16) uint16_t smem[];
+  int tv, th;
+  tile_of_block(tiles_v, tiles_h, tv, th);
+  const int m0 = tv * kTile, n0 = th * kTile;
+  f32x16_t acc[4][4];
+  gemm_tile(dzT, T_pad, vc, hTc, T_pad, H, nact[1], m0, n0, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    const int col = n0 + acc_col(wn, nb, lane);
+    if (col >= H) continue;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = m0 + acc_row(wm, mb, i, lane);
+        if (row < vc) {
+          const int64_t o = int64_t(v0 + row) * H + col;
+          if constexpr (OUT_BF16) reinterpret_cast<uint16_t*>(dW)[o] = f32_to_bf16(acc[mb][nb][i]);
+          else reinterpret_cast<float*>(dW)[o] = acc[mb][nb][i];
+        }
+      }
+  }
+}
+
+// dhidden[t] = bf16(dh_acc[pos[t]]) or +0.  One workgroup per token row.
+__global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh_acc, const int32_t* __restrict__ pos,
+                                                    int H, uint16_t* __restrict__ dhidden) {
+  const int64_t t = blockIdx.x;
+  const int j = pos[t];
+  uint16_t* out = dhidden + t * H;
+  if (j < 0) {
+    for (int k = threadIdx.x; k < H; k += 256) out[k] = 0;
+  } else {
+    const float* src = dh_acc + int64_t(j) * H;
+    for (int k = threadIdx.x; k < H; k += 256) out[k] = f32_to_bf16(src[k]);
+  }
+}
+
+static aero_status set_lds(const void* fn) {
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(kGemmLdsBytes)) == hipSuccess
+             ? AERO_OK : AERO_ERR_HIP;
+}
+
+}  // namespace aero
+
+extern "C" aero_status aero_lmhead_logprob_fused(
+    const void* hidden, const void* weight, int64_t T, int32_t H, int32_t V, const int32_t* targets,
+    float* logprob, float* entropy, float* lse, const float* old_logprob, const int32_t* token_rollout,
+    const float* adv, const float* weight_rollout, int32_t R, float eps_lo, float eps_hi, float grad_scale,
+    float* loss, float* clip_frac, void* dhidden, void* dweight, int32_t dweight_dtype, int32_t* err_flag,
+    void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace aero;
+  if (T < 0 || T > 0x7fffff00LL || V < 1 || V > (1 << 24) || H < 8 || H % 8 != 0 || H > (1 << 20) || R < 0)
+    return AERO_ERR_SHAPE;
+  const bool bwd = old_logprob != nullptr;
+  if (bwd && dweight_dtype != AERO_F32 && dweight_dtype != AERO_BF16) return AERO_ERR_DTYPE;
+  if (!weight) return AERO_ERR_NULL;
+  if (T > 0 && (!hidden || !targets || !logprob || !lse)) return AERO_ERR_NULL;
+  if (bwd && (!loss || !dweight || (T > 0 && (!token_rollout || !adv || !weight_rollout || !dhidden))))
+    return AERO_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(hidden) % 16 || reinterpret_cast<uintptr_t>(weight) % 16) return AERO_ERR_ALIGN;
+  const FusedPlan p = make_plan(T, V, H);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kWsAlign || workspace_bytes < p.total)
+    return AERO_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  const uint16_t* Wp = reinterpret_cast<const uint16_t*>(weight);
+  const uint16_t* Hp = reinterpret_cast<const uint16_t*>(hidden);
+  float* part_m = reinterpret_cast<float*>(ws + p.off_part);
+  float* part_s = part_m + size_t(p.tiles_v) * p.T_pad;
+  float* part_sz = part_s + size_t(p.tiles_v) * p.T_pad;
+  const int tiles_t = int(p.T_pad / kTile);
+
+  static bool attr_done = false;   // raising the dynamic-LDS limit is per function, once per process
+  if (!attr_done) {
+    if (set_lds(reinterpret_cast<const void*>(k_fused_stats)) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_fused_dz)) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_gemm_dh)) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_gemm_dw<true>)) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_gemm_dw<false>)) != AERO_OK)
+      return AERO_ERR_HIP;
+    attr_done = true;
+  }
+
+  // ---- forward ----
+  if (T > 0) {
+    hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(p.tiles_v * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, Hp,
+                       V, T, H, p.tiles_v, tiles_t, p.T_pad, part_m, part_s, part_sz);
+    hipLaunchKernelGGL(k_fused_combine, dim3(unsigned((T + 3) / 4)), dim3(256), 0, s, Wp, Hp, V, T, H, p.tiles_v,
+                       p.T_pad, part_m, part_s, part_sz, targets, logprob, entropy, lse, err_flag);
+  }
+  if (!bwd) return launch_status();
+
+  // ---- loss and g_t ----
+  float* g = reinterpret_cast<float*>(ws + p.off_g);
+  float* term = reinterpret_cast<float*>(ws + p.off_term);
+  int32_t* flag = reinterpret_cast<int32_t*>(ws + p.off_flag);
+  aero_status st = token_terms_from_logprob(T, V, targets, logprob, old_logprob, token_rollout, adv, weight_rollout,
+                                            R, eps_lo, eps_hi, grad_scale, g, term, flag, loss, clip_frac, err_flag, s);
+  if (st != AERO_OK) return st;
+
+  // ---- compaction and operand copies ----
+  int32_t* idx = reinterpret_cast<int32_t*>(ws + p.off_idx);
+  int32_t* pos = reinterpret_cast<int32_t*>(ws + p.off_pos);
+  int32_t* nact = reinterpret_cast<int32_t*>(ws + p.off_nact);
+  float* gc = reinterpret_cast<float*>(ws + p.off_gc);
+  float* lsec = reinterpret_cast<float*>(ws + p.off_lsec);
+  int32_t* yc = reinterpret_cast<int32_t*>(ws + p.off_yc);
+  uint16_t* hc = reinterpret_cast<uint16_t*>(ws + p.off_hc);
+  uint16_t* hTc = reinterpret_cast<uint16_t*>(ws + p.off_hTc);
+  uint16_t* WT = reinterpret_cast<uint16_t*>(ws + p.off_WT);
+  uint16_t* dz = reinterpret_cast<uint16_t*>(ws + p.off_dz);
+  uint16_t* dzT = reinterpret_cast<uint16_t*>(ws + p.off_dzT);
+  float* dh_acc = reinterpret_cast<float*>(ws + p.off_dhacc);
+
+  hipLaunchKernelGGL(k_compact_tokens, dim3(1), dim3(1024), 0, s, g, lse, targets, T, p.T_pad, idx, pos, nact, gc,
+                     lsec, yc);
+  // hidden rows gathered to hc [T_pad, H] and transposed to hTc [H, T_pad]
+  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.T_pad / 64), unsigned((H + 63) / 64)), dim3(256), 0, s, Hp,
+                     int64_t(H), T, H, idx, p.T_pad, hTc, p.T_pad, hc, int64_t(H));
+  // weight transposed to WT [H, V_ld]; rows V..V_ld of the source do not exist -> zero columns
+  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.V_ld / 64), unsigned((H + 63) / 64)), dim3(256), 0, s, Wp,
+                     int64_t(H), int64_t(V), H, nullptr, int64_t(p.V_ld), WT, int64_t(p.V_ld), nullptr, int64_t(0));
+
+  // ---- per vocabulary chunk ----
+  const int tiles_h = (H + kTile - 1) / kTile;
+  int chunk_no = 0;
+  for (int v0 = 0; v0 < V; v0 += p.VC, ++chunk_no) {
+    const int vc = (V - v0 < p.VC) ? V - v0 : p.VC;
+    const int tiles_vc = (vc + kTile - 1) / kTile;
+    const int vc8 = (vc + 7) / 8 * 8;
+    hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hc, V, H,
+                       v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, dz, dzT);
+    hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(tiles_t * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dz, p.VC, WT,
+                       int64_t(p.V_ld), v0, vc8, H, tiles_t, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
+    if (dweight_dtype == AERO_BF16)
+      hipLaunchKernelGGL((k_gemm_dw<true>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
+                         hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
+    else
+      hipLaunchKernelGGL((k_gemm_dw<false>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
+                         hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
+  }
+  if (T > 0)
+    hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, H,
+                       reinterpret_cast<uint16_t*>(dhidden));
+  return launch_status();
 }
