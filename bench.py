@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
@@ -55,6 +55,8 @@ def main():
     torch.cuda.set_device(0)
 
     name = args.workload
+    if name in ("cfg4", "cfg5"):
+        return bench_fused(args, torch, ai, aero, binding)
     wl = ai.make_config("cfg2" if name == "cfg2-dense" else name)
     if name == "cfg2-dense":   # same tensor shape, every slot a valid token
         wl.lengths[:] = wl.T // wl.R
@@ -201,6 +203,108 @@ def main():
         out["cpu_baseline"] = {"value": done / tc, "unit": "tokens/s", "cores": 1, "kind": "oracle",
                                "sample": "%d valid token rows of the same workload (every %d-th 64-row block), "
                                          "all three steps, numpy float64 single thread" % (done, stride)}
+    print(json.dumps(out))
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+
+
+def bench_fused(args, torch, ai, aero, binding):
+    """Fused LM-head workloads: one step = group advantages + fused forward + loss + dhidden/dweight."""
+    dev = "cuda:0"
+    wl = ai.make_config(args.workload)
+    T, H, V, R, Q = wl.T, wl.H, wl.V, wl.R, wl.Q
+    t0 = time.time()
+
+    def up_rows(gen, n, width):
+        out = torch.empty((n, width), dtype=torch.bfloat16, device=dev)
+        for r0 in range(0, n, 8192):
+            r1 = min(n, r0 + 8192)
+            out[r0:r1].copy_(torch.from_numpy(gen(r0, r1, threads=args.gen_threads).view(np.int16)).view(torch.bfloat16))
+        return out
+
+    hidden = up_rows(wl.hidden_rows, T, H)
+    weight = up_rows(wl.weight_rows, V, H)
+    gen_s = time.time() - t0
+
+    def d(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+
+    rewards, lengths, offsets = d(wl.rewards), d(wl.lengths), d(wl.group_offsets)
+    keys = d(wl.keep_priority.view(np.int32))
+    targets, token_rollout = d(wl.targets), d(wl.token_rollout)
+    params = aero.AdvParams(**wl.adv_params)
+    adv, wgt = torch.empty(R, device=dev), torch.empty(R, device=dev)
+    keep_mask = torch.empty(R, dtype=torch.uint8, device=dev)
+    kept_index = torch.empty(R, dtype=torch.int32, device=dev)
+    kept_offsets = torch.empty(Q + 1, dtype=torch.int32, device=dev)
+    zero_var = torch.empty(Q, dtype=torch.uint8, device=dev)
+    category = torch.empty(Q, dtype=torch.uint8, device=dev)
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    lp, ent, lse = (torch.empty(T, device=dev) for _ in range(3))
+    loss, clip = torch.empty(1, device=dev), torch.empty(1, device=dev)
+    dh = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
+    dw = torch.empty((V, H), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=T, V=V, H=H, R=R), dtype=torch.uint8,
+                     device=dev)
+
+    def step_adv():
+        aero.aero_group_advantage(rewards, lengths, offsets, keys, Q, R, params, adv, wgt, keep_mask, kept_index,
+                                  kept_offsets, zero_var, category, err)
+
+    def step_fwd_only():
+        aero.aero_lmhead_logprob_fused(hidden, weight, T, H, V, targets, lp, ent, lse, workspace=ws, err_flag=err)
+
+    def step_full():
+        aero.aero_lmhead_logprob_fused(hidden, weight, T, H, V, targets, lp, ent, lse, old_lp, token_rollout, adv,
+                                       wgt, R, wl.eps, wl.eps, 1.0, loss, clip, dh, dw, ws, err)
+
+    step_adv()
+    step_fwd_only()
+    torch.cuda.synchronize()
+    old_lp = d(ai.draw_old_logprob(lp.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps))
+    for _ in range(args.warmup):
+        step_adv(); step_full()
+    torch.cuda.synchronize()
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    t0 = time.perf_counter()
+    for k in range(K):
+        step_adv()
+        ev[k][0].record(); step_full(); ev[k][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_fused = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    # forward alone, for the split
+    ef = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(3)]
+    for a, b in ef:
+        a.record(); step_fwd_only(); b.record()
+    torch.cuda.synchronize()
+    ms_fwd = float(np.mean([a.elapsed_time(b) for a, b in ef]))
+    assert int(err.item()) == 0 and np.isfinite(loss.item())
+
+    adv_h = adv.cpu().numpy()
+    tr = wl.token_rollout
+    signal = int(((tr >= 0) & (adv_h[np.maximum(tr, 0)] != 0)).sum())
+    n_grad = int(round(signal * (1.0 - clip.item())))
+    flops = 2.0 * T * V * H + 6.0 * n_grad * V * H
+    tf = flops / (ms_fused * 1e-3) / 1e12
+    tf_fwd = 2.0 * T * V * H / (ms_fwd * 1e-3) / 1e12
+    out = {
+        "metric": "tokens/s, fused LM-head GRPO logprob+loss fwd/bwd at V=%d, H=%d" % (V, H),
+        "value": wl.n_valid * K / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "H": H, "V": V, "queries": Q, "rollouts": R,
+                   "signal_rows": signal, "grad_rows": n_grad, "input_gen_s": round(gen_s, 1)},
+        "kernels_ms": {"fused_fwd_bwd_call": ms_fused, "fused_fwd_only_call": ms_fwd},
+        "roofline": {"kernel": "whole aero_lmhead_logprob_fused call (fwd + bwd), algorithmic flops "
+                               "2TVH + 6 T_grad VH", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "roofline_fwd": {"kernel": "fused forward call", "bound": "mfma", "achieved": tf_fwd,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf_fwd / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": None},
+    }
     print(json.dumps(out))
 
 

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_stats(
   tile_of_block(tiles_v, tiles_t, tv, tt);
   const int m0 = tv * kTile, n0 = tt * kTile;
   f32x16_t acc[4][4];
-  gemm_tile(W, H, V, Hd, H, int(T), H, m0, n0, smem, acc);
+  gemm_tile_auto(W, H, V, Hd, H, int(T), H, m0, n0, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_dz(
   const int m0 = tv * kTile, n0 = tt * kTile;
   if (n0 >= nact[1]) return;   // beyond the active tokens: uniform exit
   f32x16_t acc[4][4];
-  gemm_tile(W + int64_t(v0) * H, H, vc, Hc, H, int(T_pad), H, m0, n0, smem, acc);
+  gemm_tile_auto(W + int64_t(v0) * H, H, vc, Hc, H, int(T_pad), H, m0, n0, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dh(
   const int m0 = tt * kTile, n0 = th * kTile;
   if (m0 >= nact[1]) return;
   f32x16_t acc[4][4];
-  gemm_tile(dz, VC, int(T_pad), WT + v0, V_ld, H, vc8, m0, n0, smem, acc);
+  gemm_tile_auto(dz, VC, int(T_pad), WT + v0, V_ld, H, vc8, m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dw(
   tile_of_block(tiles_v, tiles_h, tv, th);
   const int m0 = tv * kTile, n0 = th * kTile;
   f32x16_t acc[4][4];
-  gemm_tile(dzT, T_pad, vc, hTc, T_pad, H, nact[1], m0, n0, smem, acc);
+  gemm_tile_auto(dzT, T_pad, vc, hTc, T_pad, H, nact[1], m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 #pragma unroll
