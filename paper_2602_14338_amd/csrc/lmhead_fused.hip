@@ -40,6 +40,20 @@ struct FusedPlan {
       off_hc, off_hTc, off_WT, off_dz, off_dzT, off_dhacc, total;
 };
 
+// dhidden is accumulated as S split-K partials of the active rows, S chosen on the device so
+// that (active token tiles) x (H tiles) x S fills the launch grid; the buffer holds S stacked
+// copies of the active rows, never more rows than the launch grid covers.
+constexpr int kDhGridMin = 1024;
+static int dh_grid(int64_t T_pad, int H) {   // covers every tile even when all tokens are active
+  const int tiles_h = (H + kTile - 1) / kTile;
+  const int64_t all = (T_pad / kTile) * tiles_h;
+  return int(all > kDhGridMin ? all : kDhGridMin);
+}
+static int64_t dh_part_rows(int64_t T_pad, int H) {
+  const int tiles_h = (H + kTile - 1) / kTile;
+  return int64_t(dh_grid(T_pad, H) / tiles_h + 1) * kTile;   // >= S * active rows for every S
+}
+
 static FusedPlan make_plan(int64_t T, int V, int H) {
   FusedPlan p{};
   p.T = T;
@@ -48,8 +62,8 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.V_ld = int(up(size_t(V), kTile));
   p.H = H;
   p.tiles_v = p.V_ld / kTile;
-  // chunk so that dz and its transpose (2 x T_pad x VC bf16) stay around 256 MiB in total
-  int64_t vc = (int64_t(64) << 20) / p.T_pad / kTile * kTile;
+  // chunk so that dz and its transpose (T_pad x VC bf16 each) take at most 1 GiB each
+  int64_t vc = (int64_t(512) << 20) / p.T_pad / kTile * kTile;
   if (vc < kTile) vc = kTile;
   if (vc > p.V_ld) vc = p.V_ld;
   p.VC = int(vc);
@@ -70,7 +84,7 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.off_WT = take(size_t(H) * p.V_ld * 2);
   p.off_dz = take(size_t(p.T_pad) * p.VC * 2);
   p.off_dzT = take(size_t(p.VC) * p.T_pad * 2);
-  p.off_dhacc = take(size_t(p.T_pad) * H * 4);
+  p.off_dhacc = take(size_t(dh_part_rows(p.T_pad, H)) * H * 4);
   p.total = o;
   return p;
 }
@@ -84,7 +98,7 @@ size_t fused_workspace_bytes(int64_t T, int32_t V, int32_t H) {
 // forward: per-tile softmax partials
 // ------------------------------------------------------------------------------------------
 // grid: tiles_v * tiles_t workgroups.  part_* are [tiles_v][T_pad].
-__global__ __launch_bounds__(kGemmNT, 1) void k_fused_stats(
+__global__ __launch_bounds__(kGemmNT, 2) void k_fused_stats(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hd, int V, int64_t T, int H,
     int tiles_v, int tiles_t, int64_t T_pad, float* __restrict__ part_m, float* __restrict__ part_s,
     float* __restrict__ part_sz) {
@@ -92,18 +106,18 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_stats(
   int tv, tt;
   tile_of_block(tiles_v, tiles_t, tv, tt);
   const int m0 = tv * kTile, n0 = tt * kTile;
-  f32x16_t acc[4][4];
+  Acc acc;
   gemm_tile_auto(W, H, V, Hd, H, int(T), H, m0, n0, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
   const bool full = m0 + kTile <= V;
-  RowStat st[4];
+  RowStat st[kNB];
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
+  for (int nb = 0; nb < kNB; ++nb) {
     st[nb] = stat_identity();
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
+    for (int mb = 0; mb < kMB; ++mb) {
       if (full) {
         float z[16];
 #pragma unroll
@@ -121,17 +135,17 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_stats(
     st[nb] = stat_merge(st[nb], stat_shfl_xor(st[nb], 32));   // the two row-halves of the block
   }
   // the two waves that share these token columns (wm = 0, 1) merge through LDS
-  RowStat* xch = reinterpret_cast<RowStat*>(smem);   // [2 (wn)][128]
+  RowStat* xch = reinterpret_cast<RowStat*>(smem);   // [256 token columns]
   if (wm == 1 && lane < 32) {
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) xch[wn * 128 + nb * 32 + lane] = st[nb];
+    for (int nb = 0; nb < kNB; ++nb) xch[wn * 64 + nb * 32 + lane] = st[nb];
   }
   __syncthreads();
   if (wm == 0 && lane < 32) {
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-      const RowStat r = stat_merge(st[nb], xch[wn * 128 + nb * 32 + lane]);
-      const int64_t t = n0 + wn * 128 + nb * 32 + lane;   // < T_pad
+    for (int nb = 0; nb < kNB; ++nb) {
+      const RowStat r = stat_merge(st[nb], xch[wn * 64 + nb * 32 + lane]);
+      const int64_t t = n0 + wn * 64 + nb * 32 + lane;   // < T_pad
       const int64_t o = int64_t(tv) * T_pad + t;
       part_m[o] = r.m;
       part_s[o] = r.s;
@@ -263,7 +277,7 @@ __global__ __launch_bounds__(256) void k_gather_transpose(
 // ------------------------------------------------------------------------------------------
 // z^T tile rows = vocab [v0 + m0, ...), columns = compacted tokens.  dz[t][v - v0] and
 // dzT[v - v0][t] in bf16; entries outside the vocabulary or the active tokens are zero.
-__global__ __launch_bounds__(kGemmNT, 1) void k_fused_dz(
+__global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hc, int V, int H, int v0, int vc,
     int tiles_v, int tiles_t, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
     const float* __restrict__ gc, const float* __restrict__ lsec, const int32_t* __restrict__ yc,
@@ -273,19 +287,19 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_dz(
   tile_of_block(tiles_v, tiles_t, tv, tt);
   const int m0 = tv * kTile, n0 = tt * kTile;
   if (n0 >= nact[1]) return;   // beyond the active tokens: uniform exit
-  f32x16_t acc[4][4];
+  Acc acc;
   gemm_tile_auto(W + int64_t(v0) * H, H, vc, Hc, H, int(T_pad), H, m0, n0, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
+  for (int nb = 0; nb < kNB; ++nb) {
     const int64_t t = n0 + acc_col(wn, nb, lane);
     const float g = gc[t], ng = -g;
     const float c = -lsec[t] * kLog2e;
     const int yrel = yc[t] - v0;   // row of the sampled token inside this chunk, if any
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
+    for (int mb = 0; mb < kMB; ++mb) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         float d[4];
@@ -311,29 +325,49 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_fused_dz(
 // ------------------------------------------------------------------------------------------
 // backward: the two gradient GEMMs
 // ------------------------------------------------------------------------------------------
-// dh_acc[t][h] (+)= sum_k dz[t][k] WT[h][v0 + k]     M = active tokens, N = H, K = vc
-__global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dh(
-    const uint16_t* __restrict__ dz, int VC, const uint16_t* __restrict__ WT, int64_t V_ld, int v0, int vc8,
-    int H, int tiles_t, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, int accumulate,
-    float* __restrict__ dh_acc) {
+// Split-K factor for dhidden, from the number of active token tiles (uniform, device side).
+__device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid) {
+  const int base = active_tiles * tiles_h;
+  if (base == 0) return 0;
+  const int s = grid / base;
+  return s < 1 ? 1 : s;
+}
+
+// dh_part[s][t][h] (+)= sum_{k in split s} dz[t][k] WT[h][v0 + k]   M = active tokens, N = H, K = vcK
+__global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
+    const uint16_t* __restrict__ dz, int VC, const uint16_t* __restrict__ WT, int64_t V_ld, int v0, int vcK,
+    int H, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, int accumulate,
+    float* __restrict__ dh_part) {
   extern __shared__ __align__(16) uint16_t smem[];
+  const int n_pad = nact[1];
+  const int tiles_t = n_pad / kTile;
+  const int S = dh_splits(tiles_t, tiles_h, gridDim.x);
+  const int base = tiles_t * tiles_h;
+  const int pid = blockIdx.x;
+  if (S == 0 || pid >= base * S) return;   // uniform exit
+  // consecutive hardware ids (different XCDs) take different splits of neighbouring tiles
+  const int split = pid % S;
   int tt, th;
-  tile_of_block(tiles_t, tiles_h, tt, th);
+  tile_of_index(pid / S, tiles_t, tiles_h, tt, th);
   const int m0 = tt * kTile, n0 = th * kTile;
-  if (m0 >= nact[1]) return;
-  f32x16_t acc[4][4];
-  gemm_tile_auto(dz, VC, int(T_pad), WT + v0, V_ld, H, vc8, m0, n0, smem, acc);
+  const int nslices = (vcK + kDK - 1) / kDK;
+  const int per = (nslices + S - 1) / S;
+  const int k_begin = min(vcK, split * per * kDK);
+  const int k_len = max(0, min(vcK, (split + 1) * per * kDK) - k_begin);
+  Acc acc;
+  gemm_tile_auto(dz + k_begin, VC, int(T_pad), WT + v0 + k_begin, V_ld, H, k_len, m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
+  float* out = dh_part + int64_t(split) * n_pad * H;
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
+  for (int nb = 0; nb < kNB; ++nb) {
     const int col = n0 + acc_col(wn, nb, lane);
     if (col >= H) continue;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float* p = dh_acc + int64_t(m0 + acc_row(wm, mb, i, lane)) * H + col;
+        float* p = out + int64_t(m0 + acc_row(wm, mb, i, lane)) * H + col;
         *p = accumulate ? *p + acc[mb][nb][i] : acc[mb][nb][i];
       }
   }
@@ -341,23 +375,23 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dh(
 
 // dW[v0 + m][h] = sum_t dzT[m][t] hTc[h][t]          M = vc, N = H, K = active tokens (padded)
 template <bool OUT_BF16>
-__global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dw(
+__global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
     const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int64_t T_pad, int v0, int vc, int H,
     int tiles_v, int tiles_h, const int32_t* __restrict__ nact, void* __restrict__ dW) {
   extern __shared__ __align__(16) uint16_t smem[];
   int tv, th;
   tile_of_block(tiles_v, tiles_h, tv, th);
   const int m0 = tv * kTile, n0 = th * kTile;
-  f32x16_t acc[4][4];
+  Acc acc;
   gemm_tile_auto(dzT, T_pad, vc, hTc, T_pad, H, nact[1], m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
+  for (int nb = 0; nb < kNB; ++nb) {
     const int col = n0 + acc_col(wn, nb, lane);
     if (col >= H) continue;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int row = m0 + acc_row(wm, mb, i, lane);
@@ -370,17 +404,24 @@ __global__ __launch_bounds__(kGemmNT, 1) void k_gemm_dw(
   }
 }
 
-// dhidden[t] = bf16(dh_acc[pos[t]]) or +0.  One workgroup per token row.
-__global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh_acc, const int32_t* __restrict__ pos,
-                                                    int H, uint16_t* __restrict__ dhidden) {
+// dhidden[t] = bf16(sum over the split-K partials of row pos[t]) or +0.  One workgroup per row;
+// the partials are summed in split order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh_part, const int32_t* __restrict__ pos,
+                                                    const int32_t* __restrict__ nact, int H, int tiles_h,
+                                                    int dh_grid, uint16_t* __restrict__ dhidden) {
   const int64_t t = blockIdx.x;
   const int j = pos[t];
   uint16_t* out = dhidden + t * H;
   if (j < 0) {
     for (int k = threadIdx.x; k < H; k += 256) out[k] = 0;
-  } else {
-    const float* src = dh_acc + int64_t(j) * H;
-    for (int k = threadIdx.x; k < H; k += 256) out[k] = f32_to_bf16(src[k]);
+    return;
+  }
+  const int n_pad = nact[1];
+  const int S = dh_splits(n_pad / kTile, tiles_h, dh_grid);
+  for (int k = threadIdx.x; k < H; k += 256) {
+    float acc = 0.f;
+    for (int s = 0; s < S; ++s) acc += dh_part[(int64_t(s) * n_pad + j) * H + k];
+    out[k] = f32_to_bf16(acc);
   }
 }
 
@@ -476,11 +517,11 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   for (int v0 = 0; v0 < V; v0 += p.VC, ++chunk_no) {
     const int vc = (V - v0 < p.VC) ? V - v0 : p.VC;
     const int tiles_vc = (vc + kTile - 1) / kTile;
-    const int vc8 = (vc + 7) / 8 * 8;
+    const int vcK = (vc + kDK - 1) / kDK * kDK;   // dz columns [vc, vcK) are zero, WT is zero past V
     hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hc, V, H,
                        v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, dz, dzT);
-    hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(tiles_t * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dz, p.VC, WT,
-                       int64_t(p.V_ld), v0, vc8, H, tiles_t, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
+    hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, p.VC, WT,
+                       int64_t(p.V_ld), v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
     if (dweight_dtype == AERO_BF16)
       hipLaunchKernelGGL((k_gemm_dw<true>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
                          hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
@@ -489,7 +530,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
                          hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
   }
   if (T > 0)
-    hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, H,
+    hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, nact, H, tiles_h, dh_grid(p.T_pad, H),
                        reinterpret_cast<uint16_t*>(dhidden));
   return launch_status();
 }
