@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain elementwise copy kernel over the logits tensor (known size) before the timed "
+                         "region, as the yardstick for hardware byte counters")
     return ap.parse_args()
 
 
@@ -120,6 +123,8 @@ def main():
     torch.cuda.synchronize()
     old_logprob = d(ai.draw_old_logprob(logprob.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps))
 
+    if args.calibration_copy:
+        torch.neg(logits, out=dlogits)   # one elementwise kernel: reads and writes T*ld*elt bytes
     for _ in range(args.warmup):
         step_adv(); step_fwd(); step_bwd()
     torch.cuda.synchronize()

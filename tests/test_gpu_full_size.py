@@ -1,0 +1,181 @@
+"""Full-size parity, in the launch configuration bench.py times.
+
+cfg2 and cfg3 (logits path, V = 151936): the checker runs the forward definition on every row
+that matters (threaded over rows), so log-probs, entropy, the loss and the clip fraction are
+compared in full; dlogits are compared on sampled rows plus padded / zero-advantage rows.
+cfg4 and cfg5 (fused LM head): forward statistics and dhidden are compared on sampled tokens
+(each needs only its own row of the float64 product); dweight, which needs every token, is
+checked through the invariant that its rows sum to zero over the vocabulary.
+"""
+import math
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import aero_inputs as ai
+from oracle import aero_oracle as orc
+from oracle.aero_oracle import AdvParams
+
+pytestmark = pytest.mark.gpu
+THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def gh():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_helpers
+    return gpu_helpers
+
+
+def oracle_fwd_rows(host_rows, dtype, V, targets):
+    """Checker forward on the given rows, threads over rows (numpy releases the GIL)."""
+    n = host_rows.shape[0]
+    out = np.zeros((n, 3))
+
+    def one(i):
+        out[i] = orc.logprob_row(orc.widen(host_rows[i, :V], dtype), int(targets[i]))
+
+    with ThreadPoolExecutor(THREADS) as ex:
+        list(ex.map(one, range(n)))
+    return out
+
+
+def logits_full_size(gh, name, params):
+    wl = ai.make_config(name)
+    T, V, ld = wl.T, wl.V, wl.ld
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
+    a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+    tr = wl.token_rollout
+    valid = tr >= 0
+    signal = valid & (a32[np.maximum(tr, 0)] != 0) & (w32[np.maximum(tr, 0)] != 0)
+    rng = np.random.default_rng(1234)
+    sig_rows = np.nonzero(signal)[0]
+    dead_rows = np.nonzero(~signal)[0]
+    sampled = np.sort(np.concatenate([rng.choice(sig_rows, size=min(48, len(sig_rows)), replace=False),
+                                      rng.choice(dead_rows, size=min(16, len(dead_rows)), replace=False)
+                                      if len(dead_rows) else np.zeros(0, np.int64)])).astype(np.int64)
+    keep_host = {}
+    logits = torch.empty((T, ld), dtype=torch.bfloat16, device=gh.DEV)
+    ref = np.zeros((T, 3))
+    chunk = 2048
+    for r0 in range(0, T, chunk):
+        r1 = min(T, r0 + chunk)
+        h = wl.logits_rows(r0, r1, threads=THREADS)
+        logits[r0:r1].copy_(torch.from_numpy(h.view(np.int16)).view(torch.bfloat16))
+        rows = np.nonzero(valid[r0:r1])[0]
+        ref[r0 + rows] = oracle_fwd_rows(h[rows], wl.dtype, V, wl.targets[r0 + rows])
+        for t in sampled[(sampled >= r0) & (sampled < r1)]:
+            keep_host[int(t)] = h[t - r0].copy()
+    lp_ref, ent_ref, lse_ref = ref[:, 0], ref[:, 1], ref[:, 2]
+
+    # forward, as bench.py calls it
+    active = valid.astype(np.uint8)
+    lp, ent, lse, err = gh.run_fwd(logits, T, V, ld, wl.targets, active)
+    assert err == 0
+    for got, want in ((lp, lp_ref), (ent, ent_ref), (lse, lse_ref)):
+        g = got.cpu().numpy().astype(np.float64)
+        assert np.abs(g - want).max() <= 2e-3
+        assert not g[~valid].any()
+
+    # loss + dlogits with the library's own lse, as bench.py calls it
+    old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=0.05)
+    eps = np.float32(wl.eps)
+    loss_ref, n_sig, n_clip = 0.0, 0, 0
+    g_ref = np.zeros(T)
+    for t in sig_rows:
+        term, g_ref[t], unclipped, _ = orc.token_terms(lp_ref[t], float(old[t]), float(a32[tr[t]]), float(w32[tr[t]]),
+                                                       float(eps), float(eps), 1.0)
+        loss_ref += term
+        n_sig += 1
+        n_clip += 0 if unclipped else 1
+    out = gh.run_loss_bwd(logits, T, V, ld, wl.targets, lse, old, tr, ga["adv"], ga["weight"], eps=float(eps))
+    assert out["err"] == 0
+    assert abs(out["loss"].item() - loss_ref) <= 1e-4 * abs(loss_ref)
+    assert abs(out["clip_frac"].item() - (n_clip / n_sig if n_sig else 0.0)) < 1e-6
+    lp_out = out["logprob"].cpu().numpy().astype(np.float64)
+    assert np.abs(lp_out[signal] - lp_ref[signal]).max() <= 2e-3 and not lp_out[~signal].any()
+
+    sel = sampled
+    host_sel = np.stack([keep_host[int(t)] for t in sel])
+    sub = orc.grpo_loss_bwd(host_sel, wl.dtype, V, wl.targets[sel], old[sel], tr[sel], a32, w32, eps, eps, 1.0)
+    dz = out["dlogits"][torch.from_numpy(sel).to(gh.DEV)].float().cpu().numpy().astype(np.float64)[:, :V]
+    want = sub["dlogits"]
+    assert np.abs(dz - want).max() <= 1e-2
+    assert (np.abs(dz - want) <= 1e-2 * np.abs(sub["g"])[:, None] + np.abs(want) * 2.0 ** -8 + 1e-30).all()
+    dead_sel = sub["g"] == 0
+    assert not dz[dead_sel].any()
+    # every row without signal is exactly +0 in the whole tensor
+    nz_rows = (out["dlogits"].view(torch.int16) != 0).any(dim=1).cpu().numpy()
+    assert not nz_rows[~signal].any() and nz_rows[g_ref != 0].all()
+    return wl
+
+
+def test_cfg2_full_size(gh):
+    wl = logits_full_size(gh, "cfg2", dict())
+    assert wl.T == 16384 and wl.V == 151936
+
+
+def test_cfg3_full_size(gh):
+    wl = logits_full_size(gh, "cfg3", dict())
+    assert wl.T == 32768 and wl.V == 151936
+
+
+def fused_full_size(gh, name, n_sample):
+    from test_gpu_fused import run_fused
+    wl = ai.make_config(name)
+    T, H, V = wl.T, wl.H, wl.V
+    h = wl.hidden_rows(0, T, threads=THREADS)
+    W = wl.weight_rows(0, V, threads=THREADS)
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams())
+    a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+    tr = wl.token_rollout
+    signal = (tr >= 0) & (a32[np.maximum(tr, 0)] != 0)
+    rng = np.random.default_rng(4321)
+    sel = np.sort(np.concatenate([rng.choice(np.nonzero(signal)[0], size=n_sample, replace=False),
+                                  rng.choice(np.nonzero(~signal)[0], size=8, replace=False)]))
+    W64 = orc.widen(W, "bf16")
+    z = orc.widen(h[sel], "bf16") @ W64.T                              # [n_sel, V] float64
+    ref = np.array([orc.logprob_row(z[i], int(wl.targets[t])) for i, t in enumerate(sel)])
+    # behaviour log-probs: checker log-prob + noise on sampled tokens; elsewhere the sampled token's
+    # float64 logit minus the expected log-partition of i.i.d. Gaussian logits, plus noise
+    var_z = H * wl.sigma_h ** 2 * wl.sigma_w ** 2
+    zy = np.einsum("th,th->t", orc.widen(h, "bf16"), W64[wl.targets])
+    stand_in = zy - (math.log(V) + var_z / 2)
+    stand_in[sel] = ref[:, 0]
+    old = ai.draw_old_logprob(stand_in, wl.seed, sigma=0.05)
+
+    out = run_fused(gh, wl, h, W, wl.targets, bwd=dict(old=old, adv=a32, weight=w32), dweight_dtype=torch.bfloat16)
+    assert out["err"] == 0
+    for k, col in (("logprob", 0), ("entropy", 1), ("lse", 2)):
+        got = out[k].cpu().numpy().astype(np.float64)[sel]
+        assert np.abs(got - ref[:, col]).max() <= 2e-3, k
+    eps = np.float32(0.2)
+    dh = out["dhidden"][torch.from_numpy(sel).to(gh.DEV)].float().cpu().numpy().astype(np.float64)
+    for i, t in enumerate(sel):
+        if not signal[t]:
+            assert not dh[i].any()
+            continue
+        _, g, _, _ = orc.token_terms(ref[i, 0], float(old[t]), float(a32[tr[t]]), float(w32[tr[t]]), float(eps),
+                                     float(eps), 1.0)
+        dzrow = -g * np.exp(z[i] - ref[i, 2])
+        dzrow[wl.targets[t]] += g
+        want = dzrow @ W64
+        assert np.abs(dh[i] - want).max() <= 1e-2 * np.abs(want).max() + 1e-30
+    # rows of dz sum to zero over the vocabulary, hence so do the columns of dweight
+    dw = out["dweight"].float()
+    col_sum = dw.sum(dim=0).abs().max().item()
+    col_abs = dw.abs().sum(dim=0).max().item()
+    assert col_abs > 0 and col_sum <= 1e-2 * col_abs
+    assert torch.isfinite(dw).all() and torch.isfinite(out["dhidden"].float()).all()
+    assert math.isfinite(out["loss"].item())
+
+
+def test_cfg4_full_size(gh):
+    fused_full_size(gh, "cfg4", 40)
+
+
+def test_cfg5_full_size(gh):
+    fused_full_size(gh, "cfg5", 24)
