@@ -116,6 +116,11 @@ def main():
         aero.aero_grpo_loss_bwd(logits, T, V, ld, targets, lse, old_logprob, token_rollout, adv, weight, R,
                                 wl.eps, wl.eps, 1.0, loss, clip_frac, lp_out, dlogits, ws, err)
 
+    def step_single():   # statistics, loss and dlogits in one pass over the logits
+        aero.aero_grpo_loss_bwd(logits, T, V, ld, targets, None, old_logprob, token_rollout, adv, weight, R,
+                                wl.eps, wl.eps, 1.0, loss, clip_frac, logprob, dlogits, ws, err,
+                                entropy_out=entropy, lse_out=lse)
+
     # behaviour-policy log-probs: the current ones (from an untimed forward pass, as in
     # training where they come from an earlier pass of the same kernel) plus seeded noise
     step_adv()
@@ -127,10 +132,11 @@ def main():
         torch.neg(logits, out=dlogits)   # one elementwise kernel: reads and writes T*ld*elt bytes
     for _ in range(args.warmup):
         step_adv(); step_fwd(); step_bwd()
+        step_adv(); step_single()
     torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps --------------------------------------------------
     K = args.steps
+
+    # ---- forward call + loss call (6 bytes per logit), K steps, for comparison ------------
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -140,23 +146,39 @@ def main():
         ev[k][2].record(); step_bwd()
         ev[k][3].record()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
+    wall2 = time.perf_counter() - t0
     ms_adv = float(np.mean([ev[k][0].elapsed_time(ev[k][1]) for k in range(K)]))
     ms_fwd = float(np.mean([ev[k][1].elapsed_time(ev[k][2]) for k in range(K)]))
     ms_bwd = float(np.mean([ev[k][2].elapsed_time(ev[k][3]) for k in range(K)]))
+    loss_two = loss.item()
+
+    # ---- timed region: exactly K steps of the hot path (single pass over the logits) ------
+    ev1 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        step_adv()
+        ev1[k][0].record(); step_single(); ev1[k][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_single = float(np.mean([a.elapsed_time(b) for a, b in ev1]))
     assert int(err.item()) == 0 and np.isfinite(loss.item())
+    assert abs(loss.item() - loss_two) <= 1e-5 * abs(loss_two)      # both routes give the same loss
 
     # ---- algorithmic bytes per launch ----------------------------------------------------
     n_valid = wl.n_valid
-    g_rows = int((lp_out != 0).sum().item())             # rows that carried signal
+    adv_h = adv.cpu().numpy()
+    trh = wl.token_rollout
+    g_rows = int(((trh >= 0) & (adv_h[np.maximum(trh, 0)] != 0)).sum())   # rows that carry signal
     n_grad = int(round(g_rows * (1.0 - clip_frac.item())))   # unclipped rows: read + write
     n_zero = T - n_grad                                  # write only
     row_bytes = V * elt
     fwd_bytes = n_valid * row_bytes
     bwd_bytes = n_grad * 2 * row_bytes + n_zero * row_bytes
+    single_bytes = n_valid * row_bytes + T * row_bytes   # every valid row read once, every row written once
     fwd_gbs = fwd_bytes / (ms_fwd * 1e-3) / 1e9
     bwd_gbs = bwd_bytes / (ms_bwd * 1e-3) / 1e9
+    single_gbs = single_bytes / (ms_single * 1e-3) / 1e9
     ms_step = wall / K * 1e3
     out = {
         "metric": "tokens/s, GRPO logprob+loss fwd/bwd at V=%d" % V,
@@ -167,13 +189,15 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "T_rows": T, "valid_tokens": n_valid, "V": V, "storage": wl.dtype,
                    "queries": Q, "rollouts": R, "signal_rows": g_rows, "grad_rows": n_grad,
-                   "zero_fill_rows": n_zero, "clip_eps": wl.eps, "input_gen_s": round(gen_s, 1)},
-        "kernels_ms": {"group_advantage": ms_adv, "logprob_fwd": ms_fwd, "grpo_loss_bwd": ms_bwd},
-        "roofline": {"kernel": "k_dlogits (timed as the whole aero_grpo_loss_bwd call)", "bound": "hbm",
-                     "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                   "zero_fill_rows": n_zero, "clip_eps": wl.eps, "input_gen_s": round(gen_s, 1),
+                   "step": "aero_group_advantage + aero_grpo_loss_bwd(lse=NULL, logprob/entropy/lse out)"},
+        "kernels_ms": {"group_advantage": ms_adv, "single_pass_loss_call": ms_single,
+                       "two_call_logprob_fwd": ms_fwd, "two_call_grpo_loss_bwd": ms_bwd},
+        "two_call_route": {"tokens_per_s": n_valid * K / wall2, "ms_per_step": wall2 / K * 1e3,
+                           "logprob_fwd_GBps": fwd_gbs, "dlogits_GBps": bwd_gbs},
+        "roofline": {"kernel": "k_row_single_pass (timed as the whole aero_grpo_loss_bwd call)", "bound": "hbm",
+                     "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": single_gbs / HBM_PEAK_GBS,
                      "traffic": None},
-        "roofline_fwd": {"kernel": "k_logprob_fwd", "bound": "hbm", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None},
     }
 
     # ---- CPU baseline: the float64 checker as it stands, on a bounded sample ---------------

@@ -132,11 +132,18 @@ aero_status aero_logprob_fwd(
  *   every other row (padding, ignored, A == 0, w == 0, clipped): dlogits row = +0.
  *
  * logits / dlogits  [T, ld], same dtype and ld; dlogits may alias logits (in place).
- * lse      f32[T] from aero_logprob_fwd, or NULL: then it is recomputed here.
+ * lse      f32[T] from aero_logprob_fwd, or NULL: then the statistics are computed here.  With
+ *          lse == NULL, bf16 logits, 16-byte aligned rows and 8192 <= V <= 163840 the whole call
+ *          is one pass over HBM (the row is held in registers: 4 bytes of traffic per logit);
+ *          otherwise a forward pass into the workspace precedes the gradient pass.
  * old_logprob f32[T]; token_rollout i32[T] (-1 = padding); adv, weight f32[R].
  * Outputs  loss f32[1] (deterministic: fixed-order reduction); clip_frac f32[1] or NULL
- *          (clipped tokens / tokens with A != 0 and w != 0); logprob_out f32[T] or NULL (current
- *          log-prob of tokens that carry signal, 0 elsewhere); dlogits or NULL (loss only).
+ *          (clipped tokens / tokens with A != 0 and w != 0); dlogits or NULL (loss only);
+ *          logprob_out f32[T] or NULL: current log-prob of the tokens that carry signal, 0 elsewhere;
+ *          entropy_out, lse_out f32[T] or NULL: allowed only with lse == NULL (AERO_ERR_NULL
+ *          otherwise); when either is given, logprob_out / entropy_out / lse_out are written for
+ *          every row with a valid rollout index and sampled token (as aero_logprob_fwd would),
+ *          0 elsewhere.
  * workspace: aero_workspace_bytes(AERO_OP_GRPO_LOSS_BWD, T, V, 0, R, 0).
  */
 aero_status aero_grpo_loss_bwd(
@@ -146,6 +153,7 @@ aero_status aero_grpo_loss_bwd(
     const float* adv, const float* weight, int32_t R,
     float eps_lo, float eps_hi, float grad_scale,
     float* loss, float* clip_frac /*nullable*/, float* logprob_out /*nullable*/,
+    float* entropy_out /*nullable*/, float* lse_out /*nullable*/,
     void* dlogits /*nullable*/, int32_t* err_flag /*nullable*/,
     void* workspace, size_t workspace_bytes, void* stream);
 

@@ -65,7 +65,7 @@ def _load() -> C.CDLL:
     lib.aero_logprob_fwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p]
     lib.aero_grpo_loss_bwd.restype = i32
     lib.aero_grpo_loss_bwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, i32, f32, f32, f32,
-                                       p, p, p, p, p, p, sz, p]
+                                       p, p, p, p, p, p, p, p, sz, p]
     lib.aero_lmhead_logprob_fused.restype = i32
     lib.aero_lmhead_logprob_fused.argtypes = [p, p, i64, i32, i32, p, p, p, p, p, p, p, p, i32, f32, f32, f32,
                                               p, p, p, p, i32, p, p, sz, p]
@@ -145,7 +145,7 @@ def aero_logprob_fwd(logits, T: int, V: int, ld: int, targets, row_active, logpr
 
 def aero_grpo_loss_bwd(logits, T: int, V: int, ld: int, targets, lse, old_logprob, token_rollout, adv, weight,
                        R: int, eps_lo: float, eps_hi: float, grad_scale: float, loss, clip_frac, logprob_out,
-                       dlogits, workspace, err_flag=None) -> None:
+                       dlogits, workspace, err_flag=None, entropy_out=None, lse_out=None) -> None:
     if dlogits is not None and dlogits.dtype != logits.dtype:
         raise AeroError("dlogits must have the dtype of logits")
     st = _lib.aero_grpo_loss_bwd(
@@ -154,7 +154,8 @@ def aero_grpo_loss_bwd(logits, T: int, V: int, ld: int, targets, lse, old_logpro
         _ptr(token_rollout, torch.int32, "token_rollout"), _ptr(adv, torch.float32, "adv"),
         _ptr(weight, torch.float32, "weight"), R, eps_lo, eps_hi, grad_scale,
         _ptr(loss, torch.float32, "loss"), _ptr(clip_frac, torch.float32, "clip_frac"),
-        _ptr(logprob_out, torch.float32, "logprob_out"), _ptr(dlogits, None, "dlogits"),
+        _ptr(logprob_out, torch.float32, "logprob_out"), _ptr(entropy_out, torch.float32, "entropy_out"),
+        _ptr(lse_out, torch.float32, "lse_out"), _ptr(dlogits, None, "dlogits"),
         _ptr(err_flag, torch.int32, "err_flag"), _ptr(workspace, None, "workspace"),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(logits))
     _check(st, "aero_grpo_loss_bwd")

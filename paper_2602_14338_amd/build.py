@@ -6,7 +6,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libaero_hip.so")
-SOURCES = ["aero_api.hip", "group_advantage.hip", "logprob_fwd.hip", "grpo_loss_bwd.hip", "lmhead_fused.hip"]
+SOURCES = ["aero_api.hip", "group_advantage.hip", "logprob_fwd.hip", "grpo_loss_bwd.hip", "grpo_single_pass.hip",
+           "lmhead_fused.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
          # keep the compiler from forming packed-fp32 VALU ops from scalar float code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

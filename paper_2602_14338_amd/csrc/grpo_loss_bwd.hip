@@ -13,6 +13,12 @@ namespace aero {
 aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld,
                                const int32_t* targets, const uint8_t* row_active, float* logprob,
                                float* entropy, float* lse, int32_t* err_flag, hipStream_t s);
+bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits, const void* dlogits);
+void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
+                        const float* old_logprob, const int32_t* token_rollout, const float* adv,
+                        const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
+                        float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
+                        float* lse_out, void* dlogits, int32_t* err_flag, hipStream_t s);
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
@@ -35,13 +41,16 @@ inline LossWorkspace carve(void* ws, int64_t T) {
 }
 
 // ---------------------------------------------------------------- which rows carry signal
+// stats_all: every valid row (rollout index and sampled token in range) needs statistics
 __global__ __launch_bounds__(256) void k_signal_mask(
     int64_t T, int V, const int32_t* __restrict__ targets, const int32_t* __restrict__ token_rollout,
-    const float* __restrict__ adv, const float* __restrict__ weight, int R, uint8_t* __restrict__ signal) {
+    const float* __restrict__ adv, const float* __restrict__ weight, int R, int stats_all,
+    uint8_t* __restrict__ signal) {
   const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
   if (t >= T) return;
   const int i = token_rollout[t], y = targets[t];
-  signal[t] = (i >= 0 && i < R && y >= 0 && y < V && adv[i] != 0.f && weight[i] != 0.f) ? 1 : 0;
+  const bool valid = i >= 0 && i < R && y >= 0 && y < V;
+  signal[t] = (valid && (stats_all || (adv[i] != 0.f && weight[i] != 0.f))) ? 1 : 0;
 }
 
 // ---------------------------------------------------------------- token terms
@@ -269,8 +278,8 @@ extern "C" aero_status aero_grpo_loss_bwd(
     const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
     const float* lse, const float* old_logprob, const int32_t* token_rollout, const float* adv,
     const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale, float* loss,
-    float* clip_frac, float* logprob_out, void* dlogits, int32_t* err_flag, void* workspace,
-    size_t workspace_bytes, void* stream) {
+    float* clip_frac, float* logprob_out, float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag,
+    void* workspace, size_t workspace_bytes, void* stream) {
   using namespace aero;
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
   if (dtype != AERO_BF16 && dtype != AERO_F32) return AERO_ERR_DTYPE;
@@ -286,22 +295,37 @@ extern "C" aero_status aero_grpo_loss_bwd(
     return launch_status();
   }
   const unsigned blocks = unsigned((T + 255) / 256);
+  float* lp_dst = logprob_out;   // where the token-terms step may write the signal rows' log-probs
   if (!lse) {
+    // statistics are computed here; with entropy_out / lse_out they cover every valid row
+    const int stats_all = (entropy_out || lse_out) ? 1 : 0;
+    if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
+      single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                         grad_scale, stats_all, ws.g, ws.loss_term, ws.flag, logprob_out, entropy_out, lse_out,
+                         dlogits, err_flag, s);
+      hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
+      return launch_status();
+    }
     hipLaunchKernelGGL(k_signal_mask, dim3(blocks), dim3(256), 0, s, T, V, targets, token_rollout, adv, weight,
-                       R, ws.signal);
-    aero_status st = logprob_fwd_launch(logits, dtype, T, V, ld, targets, ws.signal, ws.lp_tmp, nullptr,
-                                        ws.lse, nullptr, s);
+                       R, stats_all, ws.signal);
+    float* lse_dst = lse_out ? lse_out : ws.lse;
+    aero_status st = logprob_fwd_launch(logits, dtype, T, V, ld, targets, ws.signal,
+                                        stats_all && logprob_out ? logprob_out : ws.lp_tmp, entropy_out, lse_dst,
+                                        nullptr, s);
     if (st != AERO_OK) return st;
-    lse = ws.lse;
+    lse = lse_dst;
+    if (stats_all) lp_dst = nullptr;   // already written for every valid row by the forward pass
+  } else if (entropy_out || lse_out) {
+    return AERO_ERR_NULL;   // these outputs exist only when the statistics are computed here
   }
   if (dtype == AERO_BF16)
     hipLaunchKernelGGL((k_token_terms<true, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       ws.g, ws.loss_term, ws.flag, logprob_out, err_flag);
+                       ws.g, ws.loss_term, ws.flag, lp_dst, err_flag);
   else
     hipLaunchKernelGGL((k_token_terms<false, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       ws.g, ws.loss_term, ws.flag, logprob_out, err_flag);
+                       ws.g, ws.loss_term, ws.flag, lp_dst, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
   if (dlogits) {
     const size_t elt = dtype == AERO_BF16 ? 2 : 4;

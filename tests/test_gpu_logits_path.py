@@ -196,11 +196,11 @@ def elt_rounding(dtype, ref_abs):
 
 
 def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
-                   expect_clip=False):
+                   expect_clip=False, stats=False):
     host = wl.logits_rows(0, wl.T)
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     active = (wl.token_rollout >= 0).astype(np.uint8)
-    lp_ref, _, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets, active)
+    lp_ref, ent_ref, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets, active)
     old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=sigma_old)
     eps = np.float32(wl.eps)
     ref = orc.grpo_loss_bwd(host, wl.dtype, wl.V, wl.targets, old, wl.token_rollout, ga["adv"].astype(np.float32),
@@ -208,7 +208,7 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     d = gh.logits_to_dev(host, wl.dtype)
     lse_d = gh.dev(lse_ref.astype(np.float32)) if use_oracle_lse else None
     out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, wl.token_rollout,
-                          ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace)
+                          ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace, stats=stats)
     assert out["err"] == 0
     loss = out["loss"].item()
     assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"]), (loss, ref["loss"])
@@ -216,7 +216,13 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     if expect_clip:
         assert 0.02 < ref["clip_frac"] < 0.98
     lp = out["logprob"].cpu().numpy().astype(np.float64)
-    assert np.abs(lp - ref["logprob"]).max() <= LP_TOL
+    if stats:   # statistics for every valid row, as the forward call would give them
+        assert np.abs(lp - lp_ref).max() <= LP_TOL and not lp[active == 0].any()
+        for key, want in (("entropy", ent_ref), ("lse", lse_ref)):
+            got = out[key].cpu().numpy().astype(np.float64)
+            assert np.abs(got - want).max() <= LP_TOL and not got[active == 0].any()
+    else:
+        assert np.abs(lp - ref["logprob"]).max() <= LP_TOL
     dz = gh.to_np64(out["dlogits"])[:, :wl.V]
     want = ref["dlogits"]
     assert np.isfinite(dz).all()
@@ -241,18 +247,27 @@ def test_loss_bwd_cfg1_full(gh):
     check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, inplace=True, grad_scale=64.0)
 
 
-@pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10), (32768, 32768, 10)])
+# V >= 8192 with aligned rows takes the single-pass kernel when lse is not given: 151936 and
+# 163840 (its largest row) use 20 vectors per thread, 32768 and 8200 (ragged tail) use 8;
+# 163848 is one vector too long and falls back to forward + gradient passes, as do the others.
+@pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10), (32768, 32768, 10),
+                                        (8200, 8200, 10), (163840, 163848, 4), (163848, 163848, 4)])
 def test_loss_bwd_cfg2_reduced(gh, V, ld, slots):
     wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
     check_loss_bwd(gh, wl, dict())
     check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, expect_clip=True)
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, stats=True)
     check_loss_bwd(gh, wl, dict(), inplace=True)
+    check_loss_bwd(gh, wl, dict(), inplace=True, use_oracle_lse=False, stats=True, grad_scale=3.0)
 
 
 def test_loss_bwd_cfg3_reduced(gh):
     wl = ai.make_config("cfg3", V=151936, T=320, Q=64, len_lo=1, len_hi=12)
     ref, _ = check_loss_bwd(gh, wl, dict())
     assert (ref["g"] == 0).any() and (ref["g"] != 0).any()
+    wl = ai.make_config("cfg3", V=151936, T=320, Q=64, len_lo=1, len_hi=12)
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, stats=True)
+    check_loss_bwd(gh, wl, dict(reject_enable=1), sigma_old=0.3, use_oracle_lse=False)
     wl = ai.make_config("cfg3", V=8000, T=700, Q=64, len_lo=1, len_hi=12)
     check_loss_bwd(gh, wl, dict(reject_enable=1), sigma_old=0.3, use_oracle_lse=False, expect_clip=True)
     check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, expect_clip=True)
