@@ -5,8 +5,8 @@
 // epilogue arithmetic) hide behind the other's matrix instructions.
 //
 // Two main loops share the accumulator layout:
-//   gemm_tile_dma  operands go HBM -> LDS directly (buffer_load ... lds), ring of five
-//                  256 x 32 slices; needs K % 32 == 0 and 16-byte aligned rows
+//   gemm_tile_dma  operands go HBM -> LDS directly (buffer_load ... lds), two stages of
+//                  256 x 64 slices; needs K % 64 == 0 and 16-byte aligned rows
 //   gemm_tile      register-staged 256 x 64 slices with explicit predication; any K % 8 == 0
 #pragma once
 #include "aero_device.h"
@@ -19,7 +19,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int kTile = 256;          // tile edge in both output dimensions
 constexpr int kGemmNT = 512;        // threads per workgroup (8 waves)
 constexpr int kMB = 4, kNB = 2;     // 32 x 32 blocks per wave: 128 rows x 64 columns
-constexpr size_t kGemmLdsBytes = 163840;   // all of a CU's LDS: one workgroup per CU
+constexpr size_t kGemmLdsBytes = 131072;   // two stages of (256 + 256) x 64 bf16
 
 // Position of an accumulator element inside the 256 x 256 tile.
 //   block (mb, nb) of wave (wm in 0..1, wn in 0..3); register i of lane l:
@@ -88,6 +88,7 @@ __device__ __forceinline__ void frags_mma(const Frags& f, Acc& acc) {
 // ------------------------------------------------------------------------------------------
 constexpr int kBK = 64;
 constexpr int kSliceElems = kTile * kBK;
+static_assert(size_t(4) * kSliceElems * 2 <= kGemmLdsBytes, "double buffer must fit the LDS budget");
 constexpr int kVecPerThread = kTile * (kBK / 8) / kGemmNT;   // 4
 
 __device__ __forceinline__ void slice_load(const uint16_t* __restrict__ base, int64_t ld, int row0,
@@ -171,51 +172,51 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, int64_
 // ------------------------------------------------------------------------------------------
 // Direct-to-LDS loop.  buffer_load ... lds moves 16 bytes per lane from HBM/L2 straight into
 // LDS (lane l of a wave lands at LDS base + 16 l): no staging registers, no LDS stores, and the
-// buffer descriptor's bounds check turns rows past the operand's end into zeros.
+// buffer descriptor's bounds check turns rows past the operand's end into zeros.  Slices are
+// 256 x 64: every row contributes one full 128-byte line per slice (32-wide slices fetch half
+// lines and lose a tenth of the throughput), two stages of 64 KB.
 //
-// Completion of these loads is tracked by hand: every wave issues 4 of them per slice, so
-// waiting for "at most 4 x (slices still allowed in flight)" outstanding loads means the oldest
-// slice has landed; the barrier then makes every wave's part of it visible.  The compiler does
-// not model these dependencies, hence the explicit waits and compiler fences.
+// Completion of these loads is tracked by hand: vmcnt(0) at the top of an iteration means this
+// wave's part of the slice has landed, the barrier then makes every wave's part visible and
+// also guarantees that the other stage is no longer being read.  The compiler does not model
+// these dependencies, hence the explicit waits and compiler fences.
 // ------------------------------------------------------------------------------------------
-constexpr int kDK = 32;                          // K slice of the fast loop
-constexpr int kDStages = 5;
+constexpr int kDK = kBK;                         // K slice of the fast loop
 constexpr int kDStageElems = 2 * kTile * kDK;    // A then B
-static_assert(size_t(kDStages) * kDStageElems * 2 <= kGemmLdsBytes, "ring must fit the LDS budget");
-static_assert(size_t(4) * kSliceElems * 2 <= kGemmLdsBytes, "double buffer must fit the LDS budget");
+static_assert(size_t(2) * kDStageElems * 2 <= kGemmLdsBytes, "two stages must fit the LDS budget");
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const uint16_t* base, int64_t ld, int rows_valid, int K) {
   const int64_t bytes = rows_valid > 0 ? ((int64_t(rows_valid) - 1) * ld + K) * 2 : 0;
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, int(bytes), 0x00020000);
 }
 
-// 64-byte rows: four rows share a 256-byte bank line, chunk index swizzled with bits 2..3 of the row
-__device__ __forceinline__ int dlds_off(int row, int chunk) { return row * kDK + ((chunk ^ ((row >> 2) & 3)) << 3); }
-
 #define AERO_CFENCE() asm volatile("" ::: "memory")
 
-// Wait until at most `slices` slices (4 loads each) of this wave are still in flight, and all of
-// its LDS reads have returned.  s_waitcnt takes an immediate: vmcnt in bits 3:0 and 15:14,
-// expcnt (unused, 7) in 6:4, lgkmcnt (0) in 11:8.
-__device__ __forceinline__ void wait_slices_in_flight(int slices) {
-  if (slices >= 3) __builtin_amdgcn_s_waitcnt(0x007C);        // vmcnt(12)
-  else if (slices == 2) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8)
-  else if (slices == 1) __builtin_amdgcn_s_waitcnt(0x0074);   // vmcnt(4)
-  else __builtin_amdgcn_s_waitcnt(0x0070);                    // vmcnt(0)
+// Per-lane byte offsets of the DMA loads of one operand.  Wave w fills rows [32 w, 32 w + 32)
+// with 4 instructions of 8 rows; lane l covers row l/8 of those 8 and LDS slot l%8, and the
+// chunk that belongs in that slot is slot ^ ((row >> 1) & 7) with row = 32 w + 8 j + l/8, i.e.
+// (l % 8) ^ ((4 j + l / 16) & 7): one offset for even j, one for odd j.
+struct DmaLane {
+  uint32_t even, odd, row_step;
+};
+__device__ __forceinline__ DmaLane dma_lane(int row0, int64_t ld, int wave, int lane) {
+  const uint32_t row = uint32_t((int64_t(row0 + wave * 32 + (lane >> 3)) * ld) * 2);
+  const uint32_t c0 = uint32_t((lane & 7) ^ ((lane >> 4) & 7)), c1 = uint32_t((lane & 7) ^ ((4 + (lane >> 4)) & 7));
+  return DmaLane{row + c0 * 16, row + c1 * 16, uint32_t(8 * ld * 2)};
 }
 
-// wave w fills rows [32 w, 32 w + 32) of both operands: 2 instructions of 16 rows each.
 // The whole byte offset travels in the vector offset: the hardware bounds check covers the
 // vector offset only, not the scalar one.
-__device__ __forceinline__ void dma_issue(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, uint32_t voa,
-                                          uint32_t vob, uint32_t row_step_a, uint32_t row_step_b, int k0,
-                                          uint16_t* stage, int wave) {
+__device__ __forceinline__ void dma_issue(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, const DmaLane& la,
+                                          const DmaLane& lb, int k0, uint16_t* stage, int wave) {
   uint16_t* a_dst = stage + wave * 32 * kDK;
   uint16_t* b_dst = stage + kTile * kDK + wave * 32 * kDK;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, a_dst + j * 16 * kDK, 16, voa + uint32_t(k0 * 2) + j * row_step_a, 0, 0, 0);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, b_dst + j * 16 * kDK, 16, vob + uint32_t(k0 * 2) + j * row_step_b, 0, 0, 0);
+  for (int j = 0; j < 4; ++j) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, a_dst + j * 8 * kDK, 16,
+                                             ((j & 1) ? la.odd : la.even) + uint32_t(k0 * 2) + j * la.row_step, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, b_dst + j * 8 * kDK, 16,
+                                             ((j & 1) ? lb.odd : lb.even) + uint32_t(k0 * 2) + j * lb.row_step, 0, 0, 0);
   }
 }
 
@@ -225,16 +226,12 @@ __device__ __forceinline__ void frags_load(Frags& f, const uint16_t* stage, int 
   const int chunk = ks * 2 + (lane >> 5);
 #pragma unroll
   for (int mb = 0; mb < kMB; ++mb)
-    f.a[mb] = *reinterpret_cast<const bf16x8_t*>(As + dlds_off(wm * 128 + mb * 32 + (lane & 31), chunk));
+    f.a[mb] = *reinterpret_cast<const bf16x8_t*>(As + lds_off(wm * 128 + mb * 32 + (lane & 31), chunk));
 #pragma unroll
   for (int nb = 0; nb < kNB; ++nb)
-    f.b[nb] = *reinterpret_cast<const bf16x8_t*>(Bs + dlds_off(wn * 64 + nb * 32 + (lane & 31), chunk));
+    f.b[nb] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_off(wn * 64 + nb * 32 + (lane & 31), chunk));
 }
 
-// Slice kt is consumed from registers that were filled one half-slice earlier, so the barrier
-// at the top of iteration kt publishes slice kt + 1 (not kt): the fragment reads of the next
-// slice overlap the MFMAs of this one.  Slice kt + 4 is issued into the stage slice kt - 1
-// used; every wave has finished reading it before it passes this iteration's barrier.
 __device__ __forceinline__ void gemm_tile_dma(const uint16_t* __restrict__ A, int64_t lda, int M,
                                               const uint16_t* __restrict__ B, int64_t ldb, int N, int K,
                                               int m0, int n0, uint16_t* smem, Acc& acc) {
@@ -244,35 +241,23 @@ __device__ __forceinline__ void gemm_tile_dma(const uint16_t* __restrict__ A, in
   const int nk = K / kDK;
   if (nk == 0) return;
   const __amdgpu_buffer_rsrc_t ra = operand_rsrc(A, lda, M, K), rb = operand_rsrc(B, ldb, N, K);
-  // lane l of an instruction covers row l/4 of its 16 rows, LDS slot l%4; the chunk stored in
-  // that slot is slot ^ ((row >> 2) & 3) = (l % 4) ^ (l / 16)
-  const uint32_t chunk = uint32_t((lane & 3) ^ (lane >> 4));
-  const uint32_t voa = uint32_t((int64_t(m0 + wave * 32 + (lane >> 2)) * lda) * 2) + chunk * 16;
-  const uint32_t vob = uint32_t((int64_t(n0 + wave * 32 + (lane >> 2)) * ldb) * 2) + chunk * 16;
-  const uint32_t step_a = uint32_t(16 * lda * 2), step_b = uint32_t(16 * ldb * 2);
-#pragma unroll
-  for (int s = 0; s < kDStages - 1; ++s)
-    if (s < nk) dma_issue(ra, rb, voa, vob, step_a, step_b, s * kDK, smem + s * kDStageElems, wave);
-  constexpr int kAhead = kDStages - 1;             // slices issued ahead of the one being consumed
-  wait_slices_in_flight(min(nk, kAhead) - 1);      // slice 0 has landed
-  AERO_CFENCE();
-  __builtin_amdgcn_s_barrier();
-  AERO_CFENCE();
-  Frags f0, f1;
-  frags_load(f0, smem, 0, wm, wn, lane);
+  const DmaLane la = dma_lane(m0, lda, wave, lane), lb = dma_lane(n0, ldb, wave, lane);
+  dma_issue(ra, rb, la, lb, 0, smem, wave);
   for (int kt = 0; kt < nk; ++kt) {
-    // slices 0 .. kt + 1 have landed; the later ones already issued may stay in flight
-    wait_slices_in_flight(max(0, min(nk, kt + kAhead) - kt - 2));
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): slice kt landed, own LDS reads done
     AERO_CFENCE();
     __builtin_amdgcn_s_barrier();
     AERO_CFENCE();
-    if (kt + kDStages - 1 < nk)
-      dma_issue(ra, rb, voa, vob, step_a, step_b, (kt + kDStages - 1) * kDK,
-                smem + ((kt + kDStages - 1) % kDStages) * kDStageElems, wave);
-    frags_load(f1, smem + (kt % kDStages) * kDStageElems, 1, wm, wn, lane);
+    if (kt + 1 < nk) dma_issue(ra, rb, la, lb, (kt + 1) * kDK, smem + ((kt + 1) & 1) * kDStageElems, wave);
+    const uint16_t* st = smem + (kt & 1) * kDStageElems;
+    Frags f0, f1;   // fragment reads of the next 16-wide step overlap the MFMAs of this one
+    frags_load(f0, st, 0, wm, wn, lane);
+    frags_load(f1, st, 1, wm, wn, lane);
     frags_mma(f0, acc);
-    // after the last slice this reads a stage nobody writes any more; the values are unused
-    frags_load(f0, smem + ((kt + 1) % kDStages) * kDStageElems, 0, wm, wn, lane);
+    frags_load(f0, st, 2, wm, wn, lane);
+    frags_mma(f1, acc);
+    frags_load(f1, st, 3, wm, wn, lane);
+    frags_mma(f0, acc);
     frags_mma(f1, acc);
   }
   __syncthreads();

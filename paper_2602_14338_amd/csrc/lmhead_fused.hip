@@ -325,12 +325,22 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 // ------------------------------------------------------------------------------------------
 // backward: the two gradient GEMMs
 // ------------------------------------------------------------------------------------------
-// Split-K factor for dhidden, from the number of active token tiles (uniform, device side).
+// Split-K factor for dhidden, from the number of active token tiles (uniform, device side):
+// the smallest S whose workgroup count base * S fills whole rounds of the 256 CUs best.
 __device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid) {
   const int base = active_tiles * tiles_h;
   if (base == 0) return 0;
-  const int s = grid / base;
-  return s < 1 ? 1 : s;
+  int best = 1;
+  float best_eff = 0.f;
+  for (int s = 1; base * s <= grid && s <= 64; ++s) {
+    const int wg = base * s;
+    const float eff = float(wg) / float((wg + 255) / 256 * 256);
+    if (eff > best_eff + 0.01f) {
+      best_eff = eff;
+      best = s;
+    }
+  }
+  return best;
 }
 
 // dh_part[s][t][h] (+)= sum_{k in split s} dz[t][k] WT[h][v0 + k]   M = active tokens, N = H, K = vcK
