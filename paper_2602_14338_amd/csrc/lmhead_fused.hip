@@ -292,6 +292,8 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
+  // dz for this lane's columns, packed to bf16 pairs: pk[nb][mb][i4] = rows row0 .. row0 + 3
+  uint32_t pk[kNB][kMB][4][2];
 #pragma unroll
   for (int nb = 0; nb < kNB; ++nb) {
     const int64_t t = n0 + acc_col(wn, nb, lane);
@@ -310,15 +312,62 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
           if (row == yrel) v += g;
           d[j] = row < vc ? v : 0.f;
         }
-        const int row0 = m0 + acc_row(wm, mb, i4 * 4, lane);   // 4 consecutive vocab rows
-        const uint32_t lo = pack_bf16x2(d[0], d[1]), hi = pack_bf16x2(d[2], d[3]);
-        uint2 pk = {lo, hi};
-        *reinterpret_cast<uint2*>(dz + t * VC + row0) = pk;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          dzT[int64_t(row0 + j) * T_pad + t] = uint16_t((j < 2 ? lo : hi) >> ((j & 1) * 16));
+        pk[nb][mb][i4][0] = pack_bf16x2(d[0], d[1]);
+        pk[nb][mb][i4][1] = pack_bf16x2(d[2], d[3]);
       }
     }
+  }
+  // The tile leaves through LDS so that both layouts are written with 16-byte coalesced
+  // stores.  Rows are padded by 8 elements to spread the banks.
+  constexpr int kPitch = kTile + 8;
+  // ---- [token][vocab] ----
+#pragma unroll
+  for (int nb = 0; nb < kNB; ++nb) {
+    const int tcol = acc_col(wn, nb, lane);
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int row0 = acc_row(wm, mb, i4 * 4, lane);
+        uint2 two = {pk[nb][mb][i4][0], pk[nb][mb][i4][1]};
+        *reinterpret_cast<uint2*>(smem + tcol * kPitch + row0) = two;
+      }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
+    const int u = threadIdx.x + k * kGemmNT;
+    const int r = u >> 5, cchunk = u & 31;
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + cchunk * 8);
+    *reinterpret_cast<u32x4_t*>(dz + int64_t(n0 + r) * VC + m0 + cchunk * 8) = val;
+  }
+  __syncthreads();
+  // ---- [vocab][token]: neighbouring lanes swap halves so that each writes one (t, t+1) pair ----
+#pragma unroll
+  for (int nb = 0; nb < kNB; ++nb) {
+    const int tcol = acc_col(wn, nb, lane);
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const uint32_t own = pk[nb][mb][i4][h];   // rows r (low half) and r + 1 (high half) at column tcol
+          const uint32_t got = __shfl_xor(own, 1, kWave);
+          // even lane: row r at columns (tcol, tcol + 1); odd lane: row r + 1 at columns (tcol - 1, tcol)
+          const uint32_t outw = odd ? ((got >> 16) | (own & 0xffff0000u)) : ((own & 0xffffu) | (got << 16));
+          const int row = acc_row(wm, mb, i4 * 4 + h * 2, lane) + (odd ? 1 : 0);
+          *reinterpret_cast<uint32_t*>(smem + row * kPitch + (tcol & ~1)) = outw;
+        }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
+    const int u = threadIdx.x + k * kGemmNT;
+    const int r = u >> 5, cchunk = u & 31;
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + cchunk * 8);
+    *reinterpret_cast<u32x4_t*>(dzT + int64_t(m0 + r) * T_pad + n0 + cchunk * 8) = val;
   }
 }
 
@@ -435,8 +484,11 @@ __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh
   }
 }
 
-static aero_status set_lds(const void* fn) {
-  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(kGemmLdsBytes)) == hipSuccess
+// the dz kernel stages a padded 256 x 264 bf16 tile in LDS after its main loop
+constexpr size_t kDzLdsBytes = size_t(kTile) * (kTile + 8) * 2 > kGemmLdsBytes ? size_t(kTile) * (kTile + 8) * 2 : kGemmLdsBytes;
+
+static aero_status set_lds(const void* fn, size_t bytes = kGemmLdsBytes) {
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)) == hipSuccess
              ? AERO_OK : AERO_ERR_HIP;
 }
 
@@ -473,7 +525,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   static bool attr_done = false;   // raising the dynamic-LDS limit is per function, once per process
   if (!attr_done) {
     if (set_lds(reinterpret_cast<const void*>(k_fused_stats)) != AERO_OK ||
-        set_lds(reinterpret_cast<const void*>(k_fused_dz)) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_fused_dz), kDzLdsBytes) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dh)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<true>)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<false>)) != AERO_OK)
@@ -528,7 +580,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     const int vc = (V - v0 < p.VC) ? V - v0 : p.VC;
     const int tiles_vc = (vc + kTile - 1) / kTile;
     const int vcK = (vc + kDK - 1) / kDK * kDK;   // dz columns [vc, vcK) are zero, WT is zero past V
-    hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hc, V, H,
+    hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V, H,
                        v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, dz, dzT);
     hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, p.VC, WT,
                        int64_t(p.V_ld), v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
