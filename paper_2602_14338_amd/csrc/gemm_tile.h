@@ -243,23 +243,45 @@ __device__ __forceinline__ void gemm_tile_dma(const uint16_t* __restrict__ A, in
   const __amdgpu_buffer_rsrc_t ra = operand_rsrc(A, lda, M, K), rb = operand_rsrc(B, ldb, N, K);
   const DmaLane la = dma_lane(m0, lda, wave, lane), lb = dma_lane(n0, ldb, wave, lane);
   dma_issue(ra, rb, la, lb, 0, smem, wave);
-  for (int kt = 0; kt < nk; ++kt) {
+  // One iteration = one 64-wide slice = four 16-wide steps of 8 MFMAs per wave.  The order is
+  // pinned with scheduling barriers: both fragment sets of the first two steps are read up
+  // front, the next slice is requested only after the first MFMA group (issuing the 8 loads
+  // right after the barrier would hold back every wave's first MFMAs: measured 8 % slower),
+  // and the fragment reads of steps 2 and 3 are interleaved one-to-one with MFMAs.
+  auto slice = [&](int kt, bool prefetch) {
     __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): slice kt landed, own LDS reads done
     AERO_CFENCE();
     __builtin_amdgcn_s_barrier();
     AERO_CFENCE();
-    if (kt + 1 < nk) dma_issue(ra, rb, la, lb, (kt + 1) * kDK, smem + ((kt + 1) & 1) * kDStageElems, wave);
     const uint16_t* st = smem + (kt & 1) * kDStageElems;
-    Frags f0, f1;   // fragment reads of the next 16-wide step overlap the MFMAs of this one
+    Frags f0, f1;
     frags_load(f0, st, 0, wm, wn, lane);
     frags_load(f1, st, 1, wm, wn, lane);
     frags_mma(f0, acc);
+    if (prefetch) dma_issue(ra, rb, la, lb, (kt + 1) * kDK, smem + ((kt + 1) & 1) * kDStageElems, wave);
     frags_load(f0, st, 2, wm, wn, lane);
     frags_mma(f1, acc);
     frags_load(f1, st, 3, wm, wn, lane);
     frags_mma(f0, acc);
     frags_mma(f1, acc);
-  }
+    constexpr int kMfma = 0x008, kVmemRd = 0x020, kDsRd = 0x100;
+    constexpr int kFragReads = kMB + kNB, kMfmas = kMB * kNB;
+    __builtin_amdgcn_sched_group_barrier(kDsRd, 2 * kFragReads, 0);
+    __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas, 0);
+    if (prefetch) __builtin_amdgcn_sched_group_barrier(kVmemRd, 8, 0);
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+#pragma unroll
+      for (int r = 0; r < kFragReads; ++r) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas - kFragReads, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas, 0);
+  };
+  for (int kt = 0; kt + 1 < nk; ++kt) slice(kt, true);
+  slice(nk - 1, false);
   __syncthreads();
 }
 
