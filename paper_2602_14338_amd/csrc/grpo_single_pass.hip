@@ -10,7 +10,11 @@ namespace aero {
 
 constexpr int kSpNT = 1024;
 
-template <int NV>
+// NV vectors of 16 bytes per thread: the first NV - NL live in registers, the last NL in LDS
+// (filled directly by buffer_load ... lds, each lane reads back only what its own wave loaded),
+// because 20 x 4 data registers plus the working set exceed the 128 VGPRs a 1024-thread
+// workgroup may use and the overflow would otherwise go to scratch memory in HBM.
+template <int NV, int NL>
 __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
@@ -19,6 +23,9 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag) {
   __shared__ RowStat lds[kSpNT / kWave];
+  extern __shared__ __align__(16) u32x4_t parked_raw[];   // NL x kSpNT vectors (dynamic LDS)
+  u32x4_t(*parked)[kSpNT] = reinterpret_cast<u32x4_t(*)[kSpNT]>(parked_raw);
+  constexpr int NR = NV - NL;
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x;
   const int i = token_rollout[t];
@@ -59,11 +66,20 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     return;
   }
 
-  // ---- the row -> registers (addresses clamped, validity decided at use) ----
-  const u32x4_t* zv = reinterpret_cast<const u32x4_t*>(zrow);
-  u32x4_t v[NV];
+  // ---- the row -> registers.  Buffer loads: one 32-bit offset register instead of a 64-bit
+  // pointer per vector, and the descriptor's bounds check returns zeros past the row's end
+  // (validity is decided again at use).  aux = 2: non-temporal.
+  const __amdgpu_buffer_rsrc_t zsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(zrow), 0, nvec * 16, 0x00020000);
+  const uint32_t voff = uint32_t(tid) * 16u;
+  u32x4_t v[NR];
 #pragma unroll
-  for (int u = 0; u < NV; ++u) v[u] = __builtin_nontemporal_load(zv + min(tid + u * kSpNT, nvec - 1));
+  for (int u = 0; u < NR; ++u)
+    v[u] = __builtin_amdgcn_raw_buffer_load_b128(zsrc, voff + uint32_t(u) * (kSpNT * 16u), 0, 2);
+#pragma unroll
+  for (int u = NR; u < NV; ++u)   // lane l of wave w lands at parked[u - NR][64 w + l]
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(zsrc, &parked[u - NR][(tid >> 6) << 6], 16,
+                                             voff + uint32_t(u) * (kSpNT * 16u), 0, 0, 2);
   const int jt = nvec * 8 + tid;   // ragged tail shorter than one vector
   const bool has_tail = jt < V;
   const float ztail = has_tail ? bf16_to_f32(zrow[jt]) : 0.f;
@@ -71,12 +87,30 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
 
   RowStat st = stat_identity();
 #pragma unroll
-  for (int u = 0; u < NV; ++u)
+  for (int u = 0; u < NR; ++u)
+  {
     if (tid + u * kSpNT < nvec) {
       float z[8];
       unpack8(v[u], z);
       stat_update<8>(st, z);
     }
+    __builtin_amdgcn_sched_barrier(0);   // one vector at a time: keeps temporaries from piling up
+  }
+  if constexpr (NL > 0) {
+    // the compiler does not track loads that land in LDS: wait for this wave's own
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int u = NR; u < NV; ++u) {
+      if (tid + u * kSpNT < nvec) {
+        const u32x4_t pv = parked[u - NR][tid];
+        float z[8];
+        unpack8(pv, z);
+        stat_update<8>(st, z);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
   if (has_tail) {
     float z[1] = {ztail};
     stat_update<1>(st, z);
@@ -115,14 +149,25 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
   // ---- gradient row from the registers ----
   const float c = -lse * kLog2e;
   const float ng = -g;
-  u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
+  const __amdgpu_buffer_rsrc_t dsrc = __builtin_amdgcn_make_buffer_rsrc(drow, 0, nvec * 16, 0x00020000);
+  // the store offsets are formed again from an opaque copy of the lane offset; otherwise the
+  // compiler keeps all NV load offsets alive across the reduction just to reuse them here
+  uint32_t voff_st = voff;
+  asm volatile("" : "+v"(voff_st));
   const int yvec = y >> 3;
 #pragma unroll
   for (int u = 0; u < NV; ++u) {
     const int k = tid + u * kSpNT;
     if (k < nvec) {
       float z[8], d[8];
-      unpack8(v[u], z);
+      u32x4_t src;
+      if constexpr (NL > 0) {
+        if (u < NR) src = v[u < NR ? u : 0];
+        else src = parked[u >= NR ? u - NR : 0][tid];
+      } else {
+        src = v[u];
+      }
+      unpack8(src, z);
 #pragma unroll
       for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
       if (k == yvec) {
@@ -134,8 +179,9 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
       o.y = pack_bf16x2(d[2], d[3]);
       o.z = pack_bf16x2(d[4], d[5]);
       o.w = pack_bf16x2(d[6], d[7]);
-      __builtin_nontemporal_store(o, dv + k);
+      __builtin_amdgcn_raw_buffer_store_b128(o, dsrc, voff_st + uint32_t(u) * (kSpNT * 16u), 0, 2);
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (has_tail) {
     float d = ng * exp2_fast(fmaf(ztail, kLog2e, c));
@@ -160,11 +206,11 @@ void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const 
   const uint16_t* z = reinterpret_cast<const uint16_t*>(logits);
   uint16_t* dz = reinterpret_cast<uint16_t*>(dlogits);
   if (V / 8 <= 8 * kSpNT)
-    hipLaunchKernelGGL((k_row_single_pass<8>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets, old_logprob,
+    hipLaunchKernelGGL((k_row_single_pass<8, 0>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets, old_logprob,
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
                        logprob_out, entropy_out, lse_out, dz, err_flag);
   else
-    hipLaunchKernelGGL((k_row_single_pass<20>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets, old_logprob,
+    hipLaunchKernelGGL((k_row_single_pass<20, 4>), dim3(unsigned(T)), dim3(kSpNT), 4 * kSpNT * 16, s, z, T, V, ld, targets, old_logprob,
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
                        logprob_out, entropy_out, lse_out, dz, err_flag);
 }
