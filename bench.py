@@ -36,7 +36,49 @@ def parse():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy kernel over the logits tensor (known size) before the timed "
                          "region, as the yardstick for hardware byte counters")
+    ap.add_argument("--machine-ceilings", action="store_true",
+                    help="instead of the benchmark, time plain library kernels on this GPU (an elementwise copy, a "
+                         "fill, a reduction, a bf16 matmul of the LM-head shape) as context for the roofline fractions")
     return ap.parse_args()
+
+
+def machine_ceilings(torch):
+    """What plain vendor / framework kernels reach on this GPU, same footprints as the workloads.
+    Context only: none of this is part of the library's path."""
+    dev = "cuda:0"
+    T, V, H = 16384, 151936, 1536
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    src = torch.randn((T // 4, V), device=dev, generator=gen).to(torch.bfloat16)
+    src = src.repeat(4, 1)
+    dst = torch.empty_like(src)
+
+    def timed(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    nbytes = src.numel() * 2
+    out = {"what": "plain library kernels on this GPU (context for roofline fractions)"}
+    out["elementwise_copy_GBps"] = 2 * nbytes / timed(lambda: torch.neg(src, out=dst)) / 1e6
+    out["fill_GBps"] = nbytes / timed(lambda: dst.zero_()) / 1e6
+    out["row_max_read_GBps"] = nbytes / timed(lambda: torch.amax(src, dim=1)) / 1e6
+    h = torch.randn((T, H), device=dev, generator=gen).to(torch.bfloat16)
+    w = (torch.randn((V, H), device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+    ms = timed(lambda: torch.matmul(h, w.t()), reps=5)
+    out["matmul_bf16_T16384_V151936_H1536_TFLOPs"] = 2.0 * T * V * H / ms / 1e9
+    del src, dst
+    h7 = torch.randn((T, 3584), device=dev, generator=gen).to(torch.bfloat16)
+    w7 = (torch.randn((V, 3584), device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+    ms = timed(lambda: torch.matmul(h7, w7.t()), reps=3)
+    out["matmul_bf16_T16384_V151936_H3584_TFLOPs"] = 2.0 * T * V * 3584 / ms / 1e9
+    print(json.dumps(out))
 
 
 def main():
@@ -57,6 +99,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.machine_ceilings:
+        return machine_ceilings(torch)
     name = args.workload
     if name in ("cfg4", "cfg5"):
         return bench_fused(args, torch, ai, aero, binding)

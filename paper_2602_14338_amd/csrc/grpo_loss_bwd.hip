@@ -18,7 +18,7 @@ void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const 
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, hipStream_t s);
+                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, hipStream_t s);
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
@@ -28,16 +28,18 @@ struct LossWorkspace {
   float* lse;        // [T] used when the caller gives none
   float* lp_tmp;     // [T] sink for the forward pass's log-prob when lse is recomputed
   uint8_t* signal;   // [T] rows that carry signal, so the recomputing forward pass skips the rest
+  int32_t* counter;  // [1] row counter of the streaming single-pass kernel
 };
 constexpr size_t kAlign = 256;
 inline size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
-size_t loss_workspace_bytes(int64_t T) { return 6 * seg(T); }
+size_t loss_workspace_bytes(int64_t T) { return 6 * seg(T) + kAlign; }
 inline LossWorkspace carve(void* ws, int64_t T) {
   char* p = reinterpret_cast<char*>(ws);
   const size_t s = seg(T);
   return LossWorkspace{reinterpret_cast<float*>(p), reinterpret_cast<float*>(p + s),
                        reinterpret_cast<int32_t*>(p + 2 * s), reinterpret_cast<float*>(p + 3 * s),
-                       reinterpret_cast<float*>(p + 4 * s), reinterpret_cast<uint8_t*>(p + 5 * s)};
+                       reinterpret_cast<float*>(p + 4 * s), reinterpret_cast<uint8_t*>(p + 5 * s),
+                       reinterpret_cast<int32_t*>(p + 6 * s)};
 }
 
 // ---------------------------------------------------------------- which rows carry signal
@@ -302,7 +304,7 @@ extern "C" aero_status aero_grpo_loss_bwd(
     if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
                          grad_scale, stats_all, ws.g, ws.loss_term, ws.flag, logprob_out, entropy_out, lse_out,
-                         dlogits, err_flag, s);
+                         dlogits, err_flag, ws.counter, s);
       hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
       return launch_status();
     }

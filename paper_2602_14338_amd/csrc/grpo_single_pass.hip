@@ -190,6 +190,228 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Streaming variant for long rows.  One persistent 1024-thread workgroup per CU walks rows
+// t = blockIdx.x, + gridDim.x, ...  The first NL vectors of every thread live in LDS, filled by
+// buffer_load ... lds into wave-private slots; as soon as a slot has been turned into gradient
+// and stored, the same slot is refilled with the NEXT row's vector, so the CU keeps reads in
+// flight during its store phase (a workgroup of this size cannot share a CU with a second one).
+// The remaining NV - NL vectors are ordinary register loads issued at the top of a row.
+// Rows are handed out through a global counter (padding and zero-advantage rows cost far less
+// than gradient rows, a fixed stride would leave CUs idle); a workgroup always knows its next
+// row one row ahead, and leaves when the counter has passed T.
+// ------------------------------------------------------------------------------------------
+struct RowInfo {
+  int y;
+  float A, w;
+  bool valid, signal, need;
+};
+
+__device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, const int32_t* targets,
+                                            const int32_t* token_rollout, const float* adv, const float* weight,
+                                            int stats_all) {
+  RowInfo r{0, 0.f, 0.f, false, false, false};
+  if (t >= T) return r;
+  const int i = token_rollout[t];
+  r.y = targets[t];
+  r.valid = i >= 0 && i < R && r.y >= 0 && r.y < V;
+  if (r.valid) {
+    r.A = adv[i];
+    r.w = weight[i];
+  }
+  r.signal = r.valid && r.A != 0.f && r.w != 0.f;
+  r.need = r.signal || (r.valid && stats_all);
+  return r;
+}
+
+template <int NV, int NL>
+__global__ __launch_bounds__(kSpNT) void k_row_stream(
+    const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
+    const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
+    const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
+    float grad_scale, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
+    int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
+    float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter) {
+  __shared__ RowStat lds[2][kSpNT / kWave];   // alternating: one barrier per row is enough
+  __shared__ int s_next;
+  extern __shared__ __align__(16) u32x4_t slots_raw[];   // NL x kSpNT vectors
+  u32x4_t(*slots)[kSpNT] = reinterpret_cast<u32x4_t(*)[kSpNT]>(slots_raw);
+  constexpr int NR = NV - NL;
+  const int tid = threadIdx.x;
+  const int nvec = V / 8;
+  const uint32_t voff = uint32_t(tid) * 16u;
+  const u32x4_t zero = {0u, 0u, 0u, 0u};
+  const int jt = nvec * 8 + tid;   // ragged tail shorter than one vector
+  const bool has_tail = jt < V;
+
+  auto row_rsrc = [&](const uint16_t* base, int64_t row) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base + size_t(row) * size_t(ld)), 0, nvec * 16,
+                                             0x00020000);
+  };
+  auto dma_slot = [&](__amdgpu_buffer_rsrc_t src, int u) {   // lane l of wave w lands at slots[u][64 w + l]
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(src, &slots[u][(tid >> 6) << 6], 16,
+                                             voff + uint32_t(u) * (kSpNT * 16u), 0, 0, 2);
+  };
+
+  // the first gridDim.x rows are assigned by workgroup id; the counter starts at gridDim.x
+  int64_t t = blockIdx.x;
+  if (tid == 0) s_next = atomicAdd(row_counter, 1);
+  __syncthreads();
+  int64_t tn = s_next;
+  RowInfo cur = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all);
+  if (cur.need) {
+    const __amdgpu_buffer_rsrc_t src = row_rsrc(logits, t);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) dma_slot(src, u);
+  }
+
+  int reduces = 0;   // selects the LDS buffer of the next reduction
+  while (t < T) {
+    const RowInfo nxt = row_info(tn, T, V, R, targets, token_rollout, adv, weight, stats_all);
+    const uint16_t* zrow = logits + size_t(t) * size_t(ld);
+    uint16_t* drow = dlogits ? dlogits + size_t(t) * size_t(ld) : nullptr;
+    const __amdgpu_buffer_rsrc_t nsrc = row_rsrc(logits, nxt.need ? tn : t);
+    float g = 0.f, term = 0.f, lp = 0.f, ent = 0.f, lse = 0.f;
+    int flag = 0;
+    u32x4_t v[NR];
+    float ztail = 0.f;
+
+    if (cur.need) {   // uniform over the workgroup
+      const __amdgpu_buffer_rsrc_t zsrc = row_rsrc(logits, t);
+#pragma unroll
+      for (int u = 0; u < NR; ++u)
+        v[u] = __builtin_amdgcn_raw_buffer_load_b128(zsrc, voff + uint32_t(NL + u) * (kSpNT * 16u), 0, 2);
+      ztail = has_tail ? bf16_to_f32(zrow[jt]) : 0.f;
+      const float zy = bf16_to_f32(zrow[cur.y]);   // read before any thread may overwrite the row in place
+      // Loads return in order and at least NR + 1 of them were issued just above: once no more
+      // than NR memory operations are outstanding, the older loads into this wave's LDS slots
+      // have landed (the compiler does not track those; stores may retire in any order, they
+      // only make the wait longer).
+      static_assert(NR <= 15, "immediate below holds vmcnt in 4 bits");
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0x0F70 | NR);
+      asm volatile("" ::: "memory");
+      RowStat st = stat_identity();
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        if (tid + u * kSpNT < nvec) {
+          const u32x4_t pv = slots[u][tid];
+          float z[8];
+          unpack8(pv, z);
+          stat_update<8>(st, z);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one vector at a time: keeps temporaries from piling up
+      }
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        if (tid + (NL + u) * kSpNT < nvec) {
+          float z[8];
+          unpack8(v[u], z);
+          stat_update<8>(st, z);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (has_tail) {
+        float z[1] = {ztail};
+        stat_update<1>(st, z);
+      }
+      st = stat_block_reduce<kSpNT>(st, lds[reduces++ & 1]);   // its barrier also orders loads before stores
+      lse = st.m + logf(st.s);
+      lp = zy - lse;
+      ent = lse - st.sz / st.s;
+      if (cur.signal) {   // every thread computes the same scalars
+        const float rho = expf(lp - old_logprob[t]);
+        const float lo = 1.f - eps_lo, hi = 1.f + eps_hi;
+        const float clipped = fminf(fmaxf(rho, lo), hi);
+        const float s = fminf(rho * cur.A, clipped * cur.A);
+        const bool unclipped = cur.A > 0.f ? (rho <= hi) : (rho >= lo);
+        term = -cur.w * s;
+        g = unclipped ? -grad_scale * cur.w * cur.A * rho : 0.f;
+        flag = unclipped ? 1 : 2;
+      }
+    }
+    if (tid == 0) {
+      if (!cur.valid && err_flag) {
+        const int i = token_rollout[t];
+        if (i >= R || cur.y >= V) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
+      }
+      g_out[t] = g;
+      term_out[t] = term;
+      flag_out[t] = flag;
+      if (logprob_out) logprob_out[t] = lp;
+      if (entropy_out) entropy_out[t] = ent;
+      if (lse_out) lse_out[t] = lse;
+    }
+
+    if (drow && g != 0.f) {
+      const float c = -lse * kLog2e;
+      const float ng = -g;
+      const __amdgpu_buffer_rsrc_t dsrc = row_rsrc(dlogits, t);
+      uint32_t voff_st = voff;   // opaque copy: keeps the load offsets from being kept alive for reuse
+      asm volatile("" : "+v"(voff_st));
+      const int y = cur.y, yvec = y >> 3;
+      auto grad_vec = [&](const u32x4_t& src, int k) -> u32x4_t {
+        float z[8], d[8];
+        unpack8(src, z);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
+        if (k == yvec) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
+        }
+        u32x4_t o;
+        o.x = pack_bf16x2(d[0], d[1]);
+        o.y = pack_bf16x2(d[2], d[3]);
+        o.z = pack_bf16x2(d[4], d[5]);
+        o.w = pack_bf16x2(d[6], d[7]);
+        return o;
+      };
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {   // LDS part first: each slot is refilled right after its last use
+        const int k = tid + u * kSpNT;
+        const u32x4_t pv = slots[u][tid];
+        if (k < nvec) __builtin_amdgcn_raw_buffer_store_b128(grad_vec(pv, k), dsrc, voff_st + uint32_t(u) * (kSpNT * 16u), 0, 2);
+        asm volatile("" ::: "memory");
+        if (nxt.need) dma_slot(nsrc, u);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        const int k = tid + (NL + u) * kSpNT;
+        if (k < nvec) __builtin_amdgcn_raw_buffer_store_b128(grad_vec(v[u], k), dsrc, voff_st + uint32_t(NL + u) * (kSpNT * 16u), 0, 2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (has_tail) {
+        float d = ng * exp2_fast(fmaf(ztail, kLog2e, c));
+        if (jt == y) d += g;
+        drow[jt] = f32_to_bf16(d);
+      }
+    } else {
+      // this row's slots are no longer needed: make sure every read of them has returned
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+      asm volatile("" ::: "memory");
+      if (nxt.need) {
+#pragma unroll
+        for (int u = 0; u < NL; ++u) dma_slot(nsrc, u);
+      }
+      if (drow) {   // zero fill
+        u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
+        for (int k = tid; k < nvec; k += kSpNT) __builtin_nontemporal_store(zero, dv + k);
+        if (has_tail) drow[jt] = 0;
+      }
+    }
+    // hand-over: the row after the next one is drawn now (all threads have read s_next)
+    __syncthreads();
+    if (tid == 0) s_next = tn < T ? atomicAdd(row_counter, 1) : int(T);
+    __syncthreads();
+    cur = nxt;
+    t = tn;
+    tn = s_next;
+  }
+}
+
+__global__ void k_set_counter(int32_t* p, int32_t v) { *p = v; }
+
 // True when the single-pass kernel applies: bf16, 16-byte aligned rows, and a row that fits
 // the register budget of one 1024-thread workgroup.
 bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits, const void* dlogits) {
@@ -202,17 +424,33 @@ void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const 
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, hipStream_t s) {
+                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, hipStream_t s) {
   const uint16_t* z = reinterpret_cast<const uint16_t*>(logits);
   uint16_t* dz = reinterpret_cast<uint16_t*>(dlogits);
   if (V / 8 <= 8 * kSpNT)
     hipLaunchKernelGGL((k_row_single_pass<8, 0>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets, old_logprob,
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
                        logprob_out, entropy_out, lse_out, dz, err_flag);
-  else
-    hipLaunchKernelGGL((k_row_single_pass<20, 4>), dim3(unsigned(T)), dim3(kSpNT), 4 * kSpNT * 16, s, z, T, V, ld, targets, old_logprob,
+  else {
+    constexpr int NL = 9;
+    constexpr int kLdsBytes = NL * kSpNT * 16;   // 144 KB of wave-private slots
+    static bool attr_done = false;
+    if (!attr_done) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_row_stream<20, NL>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+      attr_done = true;
+    }
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      int n = 0;
+      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+    }
+    const unsigned grid = unsigned(T < cus ? T : cus);   // one persistent workgroup per CU
+    hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(1), 0, s, row_counter, int32_t(grid));
+    hipLaunchKernelGGL((k_row_stream<20, NL>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets, old_logprob,
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
-                       logprob_out, entropy_out, lse_out, dz, err_flag);
+                       logprob_out, entropy_out, lse_out, dz, err_flag, row_counter);
+  }
 }
 
 }  // namespace aero
