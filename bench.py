@@ -23,6 +23,25 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
 
+# HBM bytes per launch of the single-pass kernel on cfg2 from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for an elementwise copy of known size;
+# see profiles/logits_path_cfg2_hbm_traffic.txt).  Valid only for the kernel sources it was
+# measured on: the figure is reported only while their hash still matches.
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8587e9, "sources_sha256": "29c7c650dc1f469346032f184b17b3b46cd63ed626bb62847d97c1e342d7990c"}}
+TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
+
+
+def measured_traffic(workload):
+    import hashlib
+    rec = MEASURED_TRAFFIC.get(workload)
+    if rec is None:
+        return None
+    m = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            m.update(fh.read())
+    return rec["bytes"] if m.hexdigest() == rec["sources_sha256"] else None
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -241,7 +260,7 @@ def main():
                            "logprob_fwd_GBps": fwd_gbs, "dlogits_GBps": bwd_gbs},
         "roofline": {"kernel": "k_row_single_pass (timed as the whole aero_grpo_loss_bwd call)", "bound": "hbm",
                      "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": single_gbs / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "algorithmic_bytes": single_bytes, "traffic": measured_traffic(name)},
     }
 
     # ---- CPU baseline: the float64 checker as it stands, on a bounded sample ---------------
