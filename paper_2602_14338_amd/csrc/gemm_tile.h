@@ -185,9 +185,25 @@ constexpr int kDK = kBK;                         // K slice of the fast loop
 constexpr int kDStageElems = 2 * kTile * kDK;    // A then B
 static_assert(size_t(2) * kDStageElems * 2 <= kGemmLdsBytes, "two stages must fit the LDS budget");
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const uint16_t* base, int64_t ld, int rows_valid, int K) {
-  const int64_t bytes = rows_valid > 0 ? ((int64_t(rows_valid) - 1) * ld + K) * 2 : 0;
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, int(bytes), 0x00020000);
+// An operand of the fast loop: rows of 64-wide K slices.  Element (row, k) lives at
+//   base + (k / 64) * kstep + row * ld + k % 64
+//   row-major [rows, K]:            ld = row pitch, kstep = 64
+//   K-slab layout [K/64][rows][64]: ld = 64,        kstep = rows * 64  (a 256-row slice is one
+//                                   contiguous 32 KB block: the layout of the library's own
+//                                   intermediate operands)
+// bytes bounds the buffer: loads past it return zeros.
+struct DmaOperand {
+  const uint16_t* base;
+  int64_t ld, kstep, bytes;
+};
+__device__ __forceinline__ DmaOperand operand_row_major(const uint16_t* base, int64_t ld, int rows_valid, int K) {
+  return DmaOperand{base, ld, kDK, rows_valid > 0 ? ((int64_t(rows_valid) - 1) * ld + K) * 2 : 0};
+}
+__device__ __forceinline__ DmaOperand operand_slabs(const uint16_t* base, int64_t rows, int K) {
+  return DmaOperand{base, kDK, rows * kDK, int64_t(K / kDK) * rows * kDK * 2};
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const DmaOperand& o) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(o.base), 0, int(o.bytes), 0x00020000);
 }
 
 #define AERO_CFENCE() asm volatile("" ::: "memory")
@@ -197,26 +213,26 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const uint16_t* b
 // chunk that belongs in that slot is slot ^ ((row >> 1) & 7) with row = 32 w + 8 j + l/8, i.e.
 // (l % 8) ^ ((4 j + l / 16) & 7): one offset for even j, one for odd j.
 struct DmaLane {
-  uint32_t even, odd, row_step;
+  uint32_t even, odd, row_step, k_step;
 };
-__device__ __forceinline__ DmaLane dma_lane(int row0, int64_t ld, int wave, int lane) {
-  const uint32_t row = uint32_t((int64_t(row0 + wave * 32 + (lane >> 3)) * ld) * 2);
+__device__ __forceinline__ DmaLane dma_lane(int row0, const DmaOperand& o, int wave, int lane) {
+  const uint32_t row = uint32_t((int64_t(row0 + wave * 32 + (lane >> 3)) * o.ld) * 2);
   const uint32_t c0 = uint32_t((lane & 7) ^ ((lane >> 4) & 7)), c1 = uint32_t((lane & 7) ^ ((4 + (lane >> 4)) & 7));
-  return DmaLane{row + c0 * 16, row + c1 * 16, uint32_t(8 * ld * 2)};
+  return DmaLane{row + c0 * 16, row + c1 * 16, uint32_t(8 * o.ld * 2), uint32_t(o.kstep * 2)};
 }
 
 // The whole byte offset travels in the vector offset: the hardware bounds check covers the
 // vector offset only, not the scalar one.
 __device__ __forceinline__ void dma_issue(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, const DmaLane& la,
-                                          const DmaLane& lb, int k0, uint16_t* stage, int wave) {
+                                          const DmaLane& lb, int kt, uint16_t* stage, int wave) {
   uint16_t* a_dst = stage + wave * 32 * kDK;
   uint16_t* b_dst = stage + kTile * kDK + wave * 32 * kDK;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, a_dst + j * 8 * kDK, 16,
-                                             ((j & 1) ? la.odd : la.even) + uint32_t(k0 * 2) + j * la.row_step, 0, 0, 0);
+                                             ((j & 1) ? la.odd : la.even) + uint32_t(kt) * la.k_step + j * la.row_step, 0, 0, 0);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, b_dst + j * 8 * kDK, 16,
-                                             ((j & 1) ? lb.odd : lb.even) + uint32_t(k0 * 2) + j * lb.row_step, 0, 0, 0);
+                                             ((j & 1) ? lb.odd : lb.even) + uint32_t(kt) * lb.k_step + j * lb.row_step, 0, 0, 0);
   }
 }
 
@@ -232,16 +248,15 @@ __device__ __forceinline__ void frags_load(Frags& f, const uint16_t* stage, int 
     f.b[nb] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_off(wn * 64 + nb * 32 + (lane & 31), chunk));
 }
 
-__device__ __forceinline__ void gemm_tile_dma(const uint16_t* __restrict__ A, int64_t lda, int M,
-                                              const uint16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                              int m0, int n0, uint16_t* smem, Acc& acc) {
+__device__ __forceinline__ void gemm_tile_dma(const DmaOperand& A, const DmaOperand& B, int K, int m0, int n0,
+                                              uint16_t* smem, Acc& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   acc_zero(acc);
   const int nk = K / kDK;
   if (nk == 0) return;
-  const __amdgpu_buffer_rsrc_t ra = operand_rsrc(A, lda, M, K), rb = operand_rsrc(B, ldb, N, K);
-  const DmaLane la = dma_lane(m0, lda, wave, lane), lb = dma_lane(n0, ldb, wave, lane);
+  const __amdgpu_buffer_rsrc_t ra = operand_rsrc(A), rb = operand_rsrc(B);
+  const DmaLane la = dma_lane(m0, A, wave, lane), lb = dma_lane(n0, B, wave, lane);
   dma_issue(ra, rb, la, lb, 0, smem, wave);
   // One iteration = one 64-wide slice = four 16-wide steps of 8 MFMAs per wave.  The order is
   // pinned with scheduling barriers: both fragment sets of the first two steps are read up
@@ -258,7 +273,7 @@ __device__ __forceinline__ void gemm_tile_dma(const uint16_t* __restrict__ A, in
     frags_load(f0, st, 0, wm, wn, lane);
     frags_load(f1, st, 1, wm, wn, lane);
     frags_mma(f0, acc);
-    if (prefetch) dma_issue(ra, rb, la, lb, (kt + 1) * kDK, smem + ((kt + 1) & 1) * kDStageElems, wave);
+    if (prefetch) dma_issue(ra, rb, la, lb, kt + 1, smem + ((kt + 1) & 1) * kDStageElems, wave);
     frags_load(f0, st, 2, wm, wn, lane);
     frags_mma(f1, acc);
     frags_load(f1, st, 3, wm, wn, lane);
@@ -292,7 +307,7 @@ __device__ __forceinline__ void gemm_tile_auto(const uint16_t* __restrict__ A, i
   const bool fast = (K % kDK == 0) && (lda % 8 == 0) && (ldb % 8 == 0) &&
                     (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0) &&
                     ((int64_t(M) - 1) * lda + K) < (int64_t(1) << 31) && ((int64_t(N) - 1) * ldb + K) < (int64_t(1) << 31);
-  if (fast) gemm_tile_dma(A, lda, M, B, ldb, N, K, m0, n0, smem, acc);
+  if (fast) gemm_tile_dma(operand_row_major(A, lda, M, K), operand_row_major(B, ldb, N, K), K, m0, n0, smem, acc);
   else gemm_tile(A, lda, M, B, ldb, N, K, m0, n0, smem, acc);
 }
 

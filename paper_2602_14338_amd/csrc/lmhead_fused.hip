@@ -35,7 +35,7 @@ inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ------------------------------------------------------------------------------------------
 struct FusedPlan {
   int64_t T, T_pad;
-  int V, V_ld, H, tiles_v, VC;   // VC: vocabulary chunk of the backward pass
+  int V, V_ld, H, H_pad, tiles_v, VC;   // VC: vocabulary chunk of the backward pass
   size_t off_part, off_g, off_term, off_flag, off_idx, off_pos, off_nact, off_gc, off_lsec, off_yc,
       off_hc, off_hTc, off_WT, off_dz, off_dzT, off_dhacc, total;
 };
@@ -61,6 +61,7 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.V = V;
   p.V_ld = int(up(size_t(V), kTile));
   p.H = H;
+  p.H_pad = int(up(size_t(H), kTile));
   p.tiles_v = p.V_ld / kTile;
   // chunk so that dz and its transpose (T_pad x VC bf16 each) take at most 1 GiB each
   int64_t vc = (int64_t(512) << 20) / p.T_pad / kTile * kTile;
@@ -80,8 +81,8 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.off_lsec = take(size_t(p.T_pad) * 4);
   p.off_yc = take(size_t(p.T_pad) * 4);
   p.off_hc = take(size_t(p.T_pad) * H * 2);
-  p.off_hTc = take(size_t(H) * p.T_pad * 2);
-  p.off_WT = take(size_t(H) * p.V_ld * 2);
+  p.off_hTc = take(size_t(p.H_pad) * p.T_pad * 2);
+  p.off_WT = take(size_t(p.H_pad) * p.V_ld * 2);
   p.off_dz = take(size_t(p.T_pad) * p.VC * 2);
   p.off_dzT = take(size_t(p.VC) * p.T_pad * 2);
   p.off_dhacc = take(size_t(dh_part_rows(p.T_pad, H)) * H * 4);
@@ -242,13 +243,16 @@ __global__ __launch_bounds__(1024) void k_compact_tokens(
   }
 }
 
-// out[c][r] = in[src(r)][c] for r < n_out_rows (src = idx[r] if idx else r; src < 0 or
-// r >= rows_in_valid -> 0), c < C.  Also writes the gathered copy gath[r][c] when gath != null.
-// 64 x 64 tiles through LDS.  grid: (ceil(n_out_rows/64), ceil(C_out/64)); columns C..C_out of
-// `in` do not exist and are written as zero rows of `out`.
+// Transposes (and optionally gathers) a row-major bf16 matrix into the K-slab layout the GEMM
+// tile reads: source row r becomes K index r, source column c becomes operand row c:
+//   out[(r / 64) * C_pad * 64 + c * 64 + r % 64] = in[src(r)][c]
+// for r < n_k (src = idx[r] if idx else r; src < 0 or src >= rows_in_valid gives 0) and c < C_pad
+// (columns c >= C do not exist in `in` and give 0).  Also writes the gathered row-major copy
+// gath[r][c] (c < C) when gath != null.  64 x 64 tiles through LDS; grid (n_k / 64, C_pad / 64).
 __global__ __launch_bounds__(256) void k_gather_transpose(
-    const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows_in_valid, int C, const int32_t* __restrict__ idx,
-    int64_t n_out_rows, uint16_t* __restrict__ out, int64_t ld_out, uint16_t* __restrict__ gath, int64_t ld_gath) {
+    const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows_in_valid, int C, int C_pad,
+    const int32_t* __restrict__ idx, int64_t n_k, uint16_t* __restrict__ out, uint16_t* __restrict__ gath,
+    int64_t ld_gath) {
   __shared__ uint16_t tile[64][66];
   const int64_t r0 = int64_t(blockIdx.x) * 64;
   const int c0 = blockIdx.y * 64;
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(256) void k_gather_transpose(
     const int64_t r = r0 + rr;
     const int c = c0 + tx;
     uint16_t v = 0;
-    if (r < n_out_rows && c < C) {
+    if (r < n_k && c < C) {
       const int64_t src = idx ? int64_t(idx[r]) : r;
       if (src >= 0 && src < rows_in_valid) v = in[src * ld_in + c];
       if (gath) gath[r * ld_gath + c] = v;
@@ -265,18 +269,21 @@ __global__ __launch_bounds__(256) void k_gather_transpose(
     tile[rr][tx] = v;
   }
   __syncthreads();
+  // one K-slab holds 64 consecutive r: this block writes rows c0 .. c0+63 of slab blockIdx.x
+  uint16_t* slab = out + int64_t(blockIdx.x) * C_pad * 64;
   for (int cc = ty; cc < 64; cc += 4) {
-    const int64_t r = r0 + tx;
     const int c = c0 + cc;
-    if (r < n_out_rows && c < C) out[int64_t(c) * ld_out + r] = tile[tx][cc];
+    if (c < C_pad) slab[int64_t(c) * 64 + tx] = tile[tx][cc];
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // backward: dz tiles for one vocabulary chunk
 // ------------------------------------------------------------------------------------------
-// z^T tile rows = vocab [v0 + m0, ...), columns = compacted tokens.  dz[t][v - v0] and
-// dzT[v - v0][t] in bf16; entries outside the vocabulary or the active tokens are zero.
+// z^T tile rows = vocab [v0 + m0, ...), columns = compacted tokens.  The bf16 gradient leaves in
+// the two K-slab layouts the next two contractions read: dz as [v / 64][token][64] (K = vocab)
+// and dzT as [token / 64][v][64] (K = tokens); entries outside the vocabulary or the active
+// tokens are zero.
 __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hc, int V, int H, int v0, int vc,
     int tiles_v, int tiles_t, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
@@ -334,12 +341,14 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
       }
   }
   __syncthreads();
+  // four 64-wide slabs per tile; consecutive threads walk one slab row by row (8 x 16 bytes per
+  // row), so each slab receives one contiguous 32 KB block
 #pragma unroll
   for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
     const int u = threadIdx.x + k * kGemmNT;
-    const int r = u >> 5, cchunk = u & 31;
-    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + cchunk * 8);
-    *reinterpret_cast<u32x4_t*>(dz + int64_t(n0 + r) * VC + m0 + cchunk * 8) = val;
+    const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
+    *reinterpret_cast<u32x4_t*>(dz + (int64_t(m0 / 64 + sl) * T_pad + n0 + r) * 64 + c8 * 8) = val;
   }
   __syncthreads();
   // ---- [vocab][token]: neighbouring lanes swap halves so that each writes one (t, t+1) pair ----
@@ -365,9 +374,9 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 #pragma unroll
   for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
     const int u = threadIdx.x + k * kGemmNT;
-    const int r = u >> 5, cchunk = u & 31;
-    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + cchunk * 8);
-    *reinterpret_cast<u32x4_t*>(dzT + int64_t(m0 + r) * T_pad + n0 + cchunk * 8) = val;
+    const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
+    *reinterpret_cast<u32x4_t*>(dzT + (int64_t(n0 / 64 + sl) * VC + m0 + r) * 64 + c8 * 8) = val;
   }
 }
 
@@ -392,9 +401,9 @@ __device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid
   return best;
 }
 
-// dh_part[s][t][h] (+)= sum_{k in split s} dz[t][k] WT[h][v0 + k]   M = active tokens, N = H, K = vcK
+// dh_part[s][t][h] (+)= sum_{k in split s} dz[t][k] W[v0 + k][h]   M = active tokens, N = H, K = vcK
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
-    const uint16_t* __restrict__ dz, int VC, const uint16_t* __restrict__ WT, int64_t V_ld, int v0, int vcK,
+    const uint16_t* __restrict__ dz, const uint16_t* __restrict__ WT, int H_pad, int v0, int vcK,
     int H, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, int accumulate,
     float* __restrict__ dh_part) {
   extern __shared__ __align__(16) uint16_t smem[];
@@ -414,7 +423,9 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
   const int k_begin = min(vcK, split * per * kDK);
   const int k_len = max(0, min(vcK, (split + 1) * per * kDK) - k_begin);
   Acc acc;
-  gemm_tile_auto(dz + k_begin, VC, int(T_pad), WT + v0 + k_begin, V_ld, H, k_len, m0, n0, smem, acc);
+  // both operands are K-slabs over the vocabulary: dz of this chunk, WT of the whole vocabulary
+  gemm_tile_dma(operand_slabs(dz + int64_t(k_begin / kDK) * T_pad * kDK, T_pad, k_len),
+                operand_slabs(WT + int64_t((v0 + k_begin) / kDK) * H_pad * kDK, H_pad, k_len), k_len, m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   float* out = dh_part + int64_t(split) * n_pad * H;
@@ -435,14 +446,14 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
 // dW[v0 + m][h] = sum_t dzT[m][t] hTc[h][t]          M = vc, N = H, K = active tokens (padded)
 template <bool OUT_BF16>
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
-    const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int64_t T_pad, int v0, int vc, int H,
+    const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int VC, int H_pad, int v0, int vc, int H,
     int tiles_v, int tiles_h, const int32_t* __restrict__ nact, void* __restrict__ dW) {
   extern __shared__ __align__(16) uint16_t smem[];
   int tv, th;
   tile_of_block(tiles_v, tiles_h, tv, th);
   const int m0 = tv * kTile, n0 = th * kTile;
   Acc acc;
-  gemm_tile_auto(dzT, T_pad, vc, hTc, T_pad, H, nact[1], m0, n0, smem, acc);
+  gemm_tile_dma(operand_slabs(dzT, VC, nact[1]), operand_slabs(hTc, H_pad, nact[1]), nact[1], m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
 #pragma unroll
@@ -566,12 +577,12 @@ extern "C" aero_status aero_lmhead_logprob_fused(
 
   hipLaunchKernelGGL(k_compact_tokens, dim3(1), dim3(1024), 0, s, g, lse, targets, T, p.T_pad, idx, pos, nact, gc,
                      lsec, yc);
-  // hidden rows gathered to hc [T_pad, H] and transposed to hTc [H, T_pad]
-  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.T_pad / 64), unsigned((H + 63) / 64)), dim3(256), 0, s, Hp,
-                     int64_t(H), T, H, idx, p.T_pad, hTc, p.T_pad, hc, int64_t(H));
-  // weight transposed to WT [H, V_ld]; rows V..V_ld of the source do not exist -> zero columns
-  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.V_ld / 64), unsigned((H + 63) / 64)), dim3(256), 0, s, Wp,
-                     int64_t(H), int64_t(V), H, nullptr, int64_t(p.V_ld), WT, int64_t(p.V_ld), nullptr, int64_t(0));
+  // hidden rows gathered to hc [T_pad, H] and transposed to hTc, K-slabs over the compacted tokens
+  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.T_pad / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Hp,
+                     int64_t(H), T, H, p.H_pad, idx, p.T_pad, hTc, hc, int64_t(H));
+  // weight transposed to WT, K-slabs over the vocabulary; rows V..V_ld of the source do not exist -> zeros
+  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.V_ld / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Wp,
+                     int64_t(H), int64_t(V), H, p.H_pad, nullptr, int64_t(p.V_ld), WT, nullptr, int64_t(0));
 
   // ---- per vocabulary chunk ----
   const int tiles_h = (H + kTile - 1) / kTile;
@@ -582,14 +593,14 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     const int vcK = (vc + kDK - 1) / kDK * kDK;   // dz columns [vc, vcK) are zero, WT is zero past V
     hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V, H,
                        v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, dz, dzT);
-    hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, p.VC, WT,
-                       int64_t(p.V_ld), v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
+    hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, WT,
+                       p.H_pad, v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
     if (dweight_dtype == AERO_BF16)
       hipLaunchKernelGGL((k_gemm_dw<true>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
-                         hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
+                         hTc, p.VC, p.H_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
     else
       hipLaunchKernelGGL((k_gemm_dw<false>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
-                         hTc, p.T_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
+                         hTc, p.VC, p.H_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
   }
   if (T > 0)
     hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, nact, H, tiles_h, dh_grid(p.T_pad, H),
