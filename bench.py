@@ -379,7 +379,7 @@ def bench_fused(args, torch, ai, aero, binding):
     tr = wl.token_rollout
     signal = int(((tr >= 0) & (adv_h[np.maximum(tr, 0)] != 0)).sum())
     n_grad = int(round(signal * (1.0 - clip.item())))
-    flops = 2.0 * T * V * H + 6.0 * n_grad * V * H
+    flops = 2.0 * wl.n_valid * V * H + 6.0 * n_grad * V * H
     tf = flops / (ms_fused * 1e-3) / 1e12
     tf_fwd = 2.0 * T * V * H / (ms_fwd * 1e-3) / 1e12
     out = {
@@ -391,7 +391,7 @@ def bench_fused(args, torch, ai, aero, binding):
                    "signal_rows": signal, "grad_rows": n_grad, "input_gen_s": round(gen_s, 1)},
         "kernels_ms": {"fused_fwd_bwd_call": ms_fused, "fused_fwd_only_call": ms_fwd},
         "roofline": {"kernel": "whole aero_lmhead_logprob_fused call (fwd + bwd), algorithmic flops "
-                               "2TVH + 6 T_grad VH", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                               "2 T_valid V H + 6 T_grad V H", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
         "roofline_fwd": {"kernel": "fused forward call", "bound": "mfma", "achieved": tf_fwd,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf_fwd / MFMA_BF16_PEAK_TFLOPS,

@@ -296,7 +296,7 @@ def lmhead_fused(hidden_bits, weight_bits, targets, old_logprob=None, token_roll
         b = grpo_loss_bwd(None, "f64", V, targets, old_logprob, token_rollout, adv, weight,
                           eps_lo, eps_hi, grad_scale, want_dlogits=True, z64=z)
         dz = b["dlogits"]
-        out.update(loss=b["loss"], clip_frac=b["clip_frac"], g=b["g"],
+        out.update(loss=b["loss"], clip_frac=b["clip_frac"], g=b["g"], loss_terms=b["loss_terms"],
                    dhidden=dz @ widen(weight_bits, "bf16"),
                    dweight=dz.T @ widen(hidden_bits, "bf16"))
     return out

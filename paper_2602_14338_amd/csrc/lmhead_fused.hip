@@ -1,7 +1,9 @@
 // LM head fused into the softmax statistics, the clipped loss and its gradients: logits
 // z = hidden @ weight^T exist only as fp32 MFMA accumulator tiles.
 //
-// Forward   k_fused_stats   tile of z^T (vocab rows x token columns): every lane owns one
+// Forward   k_compact_valid rows that have a target are compacted (padding rows take no part in
+//                           any contraction; their outputs are written as zeros) and gathered
+//           k_fused_stats   tile of z^T (vocab rows x token columns): every lane owns one
 //                           token column per block, so the running (offset, sum exp,
 //                           sum exp*z) is a per-lane register recurrence with no shuffles
 //           k_fused_combine merges the per-tile partials of a token, adds the sampled
@@ -11,10 +13,11 @@
 //                             curation leaves), hidden is gathered / transposed once, weight
 //                             is transposed once, and per vocabulary chunk:
 //           k_fused_dz        recompute the z^T tile, dz = g (onehot - exp(z - lse)) -> bf16,
-//                             stored both as [token, vocab] and [vocab, token]
-//           k_gemm_dh         dhidden_acc += dz_chunk @ weight_chunk        (fp32, per chunk)
+//                             stored in the K-slab layouts [vocab/64][token][64] and
+//                             [token/64][vocab][64] that the next two contractions read
+//           k_gemm_dh         dhidden_acc += dz_chunk @ weight_chunk        (fp32 split-K partials)
 //           k_gemm_dw         dweight[chunk rows] = dz_chunk^T @ hidden     (complete per chunk)
-//           k_scatter_dh      fp32 accumulator rows -> bf16 dhidden at the original token rows
+//           k_scatter_dh      fp32 partials summed in fixed order -> bf16 dhidden at the original rows
 // All contractions use the same 256 x 256 x 64 MFMA tile with both operands K-contiguous.
 #include "gemm_tile.h"
 
@@ -36,7 +39,7 @@ inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct FusedPlan {
   int64_t T, T_pad;
   int V, V_ld, H, H_pad, tiles_v, VC;   // VC: vocabulary chunk of the backward pass
-  size_t off_part, off_g, off_term, off_flag, off_idx, off_pos, off_nact, off_gc, off_lsec, off_yc,
+  size_t off_part, off_fidx, off_nf, off_g, off_term, off_flag, off_idx, off_pos, off_nact, off_gc, off_lsec, off_yc,
       off_hc, off_hTc, off_WT, off_dz, off_dzT, off_dhacc, total;
 };
 
@@ -71,6 +74,8 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes, kWsAlign); return at; };
   p.off_part = take(size_t(3) * p.tiles_v * p.T_pad * 4);
+  p.off_fidx = take(size_t(p.T_pad) * 4);
+  p.off_nf = take(16);
   p.off_g = take(size_t(p.T_pad) * 4);
   p.off_term = take(size_t(p.T_pad) * 4);
   p.off_flag = take(size_t(p.T_pad) * 4);
@@ -96,19 +101,83 @@ size_t fused_workspace_bytes(int64_t T, int32_t V, int32_t H) {
 }
 
 // ------------------------------------------------------------------------------------------
+// forward: rows with a target, compacted
+// ------------------------------------------------------------------------------------------
+// Rows without a target (padding) take no part in the contraction.  Single workgroup,
+// order-preserving: fidx[j] = j-th row with 0 <= target < V (-1 past the count), nf[0] = count,
+// nf[1] = count rounded up to a tile.  Ignored rows get their zero outputs here; a target >= V
+// raises the device error bit.
+__global__ __launch_bounds__(1024) void k_compact_valid(
+    const int32_t* __restrict__ targets, int64_t T, int64_t T_pad, int V, int32_t* __restrict__ fidx,
+    int32_t* __restrict__ nf, float* __restrict__ logprob, float* __restrict__ entropy, float* __restrict__ lse_out,
+    int32_t* __restrict__ err_flag) {
+  __shared__ int part[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (T + 1023) / 1024;
+  const int64_t lo = min(T, tid * per), hi = min(T, lo + per);
+  int cnt = 0;
+  for (int64_t t = lo; t < hi; ++t) cnt += unsigned(targets[t]) < unsigned(V);
+  part[tid] = cnt;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = tid ? part[tid - 1] : 0;
+  const int total = part[1023];
+  bool bad = false;
+  for (int64_t t = lo; t < hi; ++t) {
+    const int y = targets[t];
+    if (unsigned(y) < unsigned(V)) {
+      fidx[run++] = int(t);
+    } else {
+      logprob[t] = 0.f;
+      lse_out[t] = 0.f;
+      if (entropy) entropy[t] = 0.f;
+      bad |= y >= V;
+    }
+  }
+  if (bad && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
+  for (int64_t j = total + tid; j < T_pad; j += 1024) fidx[j] = -1;
+  if (tid == 0) {
+    nf[0] = total;
+    nf[1] = (total + kTile - 1) / kTile * kTile;
+  }
+}
+
+// out[j][:] = in[idx[j]][:] (zeros where idx[j] < 0), H % 8 == 0, 16-byte vectors; one wave per row.
+__global__ __launch_bounds__(256) void k_gather_rows(const uint16_t* __restrict__ in, int H,
+                                                     const int32_t* __restrict__ idx, int64_t n_rows,
+                                                     uint16_t* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t j = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (j >= n_rows) return;
+  const int src = idx[j];
+  for (int k = lane * 8; k < H; k += kWave * 8) {
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (src >= 0) v = *reinterpret_cast<const u32x4_t*>(in + int64_t(src) * H + k);
+    *reinterpret_cast<u32x4_t*>(out + j * H + k) = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // forward: per-tile softmax partials
 // ------------------------------------------------------------------------------------------
-// grid: tiles_v * tiles_t workgroups.  part_* are [tiles_v][T_pad].
+// grid: tiles_v * tiles_t workgroups.  Hf holds the compacted rows ([T_pad][H], zero past the
+// count); part_* are [tiles_v][T_pad], indexed by compact row.
 __global__ __launch_bounds__(kGemmNT, 2) void k_fused_stats(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hd, int V, int64_t T, int H,
-    int tiles_v, int tiles_t, int64_t T_pad, float* __restrict__ part_m, float* __restrict__ part_s,
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hf, int V, int H, int tiles_v, int tiles_t,
+    int64_t T_pad, const int32_t* __restrict__ nf, float* __restrict__ part_m, float* __restrict__ part_s,
     float* __restrict__ part_sz) {
   extern __shared__ __align__(16) uint16_t smem[];
   int tv, tt;
   tile_of_block(tiles_v, tiles_t, tv, tt);
   const int m0 = tv * kTile, n0 = tt * kTile;
+  if (n0 >= nf[1]) return;   // beyond the rows with a target: uniform exit
   Acc acc;
-  gemm_tile_auto(W, H, V, Hd, H, int(T), H, m0, n0, smem, acc);
+  gemm_tile_auto(W, H, V, Hf, H, int(T_pad), H, m0, n0, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -155,42 +224,53 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_stats(
   }
 }
 
-// One wave per token: merge the tiles_v partials, compute the sampled token's logit.
+// 64 consecutive compact rows per workgroup.  Phase 1: lane <-> row, the tiles_v partials are
+// split over the four waves (every load is one coalesced 256-byte row segment) and merged
+// through LDS.  Phase 2: each wave takes 16 of the rows and computes the sampled token's logit
+// as a dot product of the two bf16 rows; results go to the row's original position.
+constexpr int kCombineTokens = 64;
 __global__ __launch_bounds__(256) void k_fused_combine(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hd, int V, int64_t T, int H, int tiles_v,
-    int64_t T_pad, const float* __restrict__ part_m, const float* __restrict__ part_s,
-    const float* __restrict__ part_sz, const int32_t* __restrict__ targets, float* __restrict__ logprob,
-    float* __restrict__ entropy, float* __restrict__ lse_out, int32_t* __restrict__ err_flag) {
-  const int lane = threadIdx.x & 63;
-  const int64_t t = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (t >= T) return;
-  const int y = targets[t];
-  if (y < 0 || y >= V) {   // ignored row
-    if (lane == 0) {
-      logprob[t] = 0.f;
-      lse_out[t] = 0.f;
-      if (entropy) entropy[t] = 0.f;
-      if (y >= V && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
-    }
-    return;
-  }
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hf, int H, int tiles_v, int64_t T_pad,
+    const int32_t* __restrict__ fidx, const int32_t* __restrict__ nf, const float* __restrict__ part_m,
+    const float* __restrict__ part_s, const float* __restrict__ part_sz, const int32_t* __restrict__ targets,
+    float* __restrict__ logprob, float* __restrict__ entropy, float* __restrict__ lse_out) {
+  __shared__ RowStat xs[4][kCombineTokens];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t j0 = int64_t(blockIdx.x) * kCombineTokens;   // j0 + 63 < T_pad
+  const int n = nf[0];
+  if (j0 >= n) return;
   RowStat st = stat_identity();
-  for (int tv = lane; tv < tiles_v; tv += kWave) {
-    const int64_t o = int64_t(tv) * T_pad + t;
+  for (int tv = wave; tv < tiles_v; tv += 4) {
+    const int64_t o = int64_t(tv) * T_pad + j0 + lane;
     st = stat_merge(st, RowStat{part_m[o], part_s[o], part_sz[o]});
   }
-  st = stat_wave_reduce(st);
-  float dot = 0.f;
-  const uint16_t* hr = Hd + t * H;
-  const uint16_t* wr = W + int64_t(y) * H;
-  for (int k = lane; k < H; k += kWave) dot = fmaf(bf16_to_f32(hr[k]), bf16_to_f32(wr[k]), dot);
+  xs[wave][lane] = st;
+  __syncthreads();
+  for (int k16 = 0; k16 < kCombineTokens / 4; ++k16) {
+    const int c = wave * (kCombineTokens / 4) + k16;
+    const int64_t j = j0 + c;
+    if (j >= n) break;   // uniform per wave
+    const int64_t t = fidx[j];
+    const int y = targets[t];   // 0 <= y < V by construction of fidx
+    const uint16_t* hr = Hf + j * H;
+    const uint16_t* wr = W + int64_t(y) * H;
+    float dot = 0.f;
+    for (int k = lane * 8; k < H; k += kWave * 8) {
+      float a[8], b[8];
+      unpack8(*reinterpret_cast<const u32x4_t*>(hr + k), a);
+      unpack8(*reinterpret_cast<const u32x4_t*>(wr + k), b);
 #pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, kWave);
-  if (lane == 0) {
-    const float lse = st.m + logf(st.s);
-    logprob[t] = dot - lse;
-    lse_out[t] = lse;
-    if (entropy) entropy[t] = lse - st.sz / st.s;
+      for (int e = 0; e < 8; ++e) dot = fmaf(a[e], b[e], dot);
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+    if (lane == 0) {
+      const RowStat r = stat_merge(stat_merge(xs[0][c], xs[1][c]), stat_merge(xs[2][c], xs[3][c]));
+      const float lse = r.m + logf(r.s);
+      logprob[t] = dot - lse;
+      lse_out[t] = lse;
+      if (entropy) entropy[t] = lse - r.sz / r.s;
+    }
   }
 }
 
@@ -277,6 +357,51 @@ __global__ __launch_bounds__(256) void k_gather_transpose(
   }
 }
 
+// Same contract, for C % 8 == 0, ld_in % 8 == 0 and 16-byte aligned pointers: every global access
+// is a 16-byte vector.  The tile is held in LDS as [r][c] with 32-bit writes; a thread then
+// collects 8 consecutive r of one column c for one 16-byte store, threads ordered so that a
+// workgroup writes its 64 x 64 block of the slab as one contiguous 8 KB run.
+__global__ __launch_bounds__(256) void k_gather_transpose_vec(
+    const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows_in_valid, int C, int C_pad,
+    const int32_t* __restrict__ idx, int64_t n_k, uint16_t* __restrict__ out, uint16_t* __restrict__ gath,
+    int64_t ld_gath) {
+  __shared__ uint32_t tile[64][33];   // [r][c / 2]
+  const int64_t r0 = int64_t(blockIdx.x) * 64;
+  const int c0 = blockIdx.y * 64;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int u = threadIdx.x + k * 256;
+    const int rr = u >> 3, c8 = (u & 7) * 8;
+    const int64_t r = r0 + rr;
+    const int c = c0 + c8;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (r < n_k && c < C) {
+      const int64_t src = idx ? int64_t(idx[r]) : r;
+      if (src >= 0 && src < rows_in_valid) v = *reinterpret_cast<const u32x4_t*>(in + src * ld_in + c);
+      if (gath) *reinterpret_cast<u32x4_t*>(gath + r * ld_gath + c) = v;
+    }
+    tile[rr][c8 / 2 + 0] = v.x;
+    tile[rr][c8 / 2 + 1] = v.y;
+    tile[rr][c8 / 2 + 2] = v.z;
+    tile[rr][c8 / 2 + 3] = v.w;
+  }
+  __syncthreads();
+  uint16_t* slab = out + int64_t(blockIdx.x) * C_pad * 64;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int u = threadIdx.x + k * 256;
+    const int cc = u >> 3, q = u & 7;   // column cc, K positions 8 q .. 8 q + 7
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t lo = tile[8 * q + 2 * e][cc >> 1], hi = tile[8 * q + 2 * e + 1][cc >> 1];
+      w[e] = (cc & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+    }
+    const u32x4_t v = {w[0], w[1], w[2], w[3]};
+    if (c0 + cc < C_pad) *reinterpret_cast<u32x4_t*>(slab + int64_t(c0 + cc) * 64 + 8 * q) = v;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // backward: dz tiles for one vocabulary chunk
 // ------------------------------------------------------------------------------------------
@@ -307,21 +432,36 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const float g = gc[t], ng = -g;
     const float c = -lsec[t] * kLog2e;
     const int yrel = yc[t] - v0;   // row of the sampled token inside this chunk, if any
+    // Almost every wave holds neither a sampled token's row nor rows past the vocabulary: that
+    // case (uniform over the wave) runs without the two per-element tests.
+    const bool plain = (m0 + kTile <= vc) && !__any(unsigned(yrel - m0 - wm * 128) < 128u);
+    if (plain) {
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
+      for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        float d[4];
+        for (int i4 = 0; i4 < 4; ++i4) {
+          float d[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int row = m0 + acc_row(wm, mb, i4 * 4 + j, lane);
-          float v = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
-          if (row == yrel) v += g;
-          d[j] = row < vc ? v : 0.f;
+          for (int j = 0; j < 4; ++j) d[j] = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
+          pk[nb][mb][i4][0] = pack_bf16x2(d[0], d[1]);
+          pk[nb][mb][i4][1] = pack_bf16x2(d[2], d[3]);
         }
-        pk[nb][mb][i4][0] = pack_bf16x2(d[0], d[1]);
-        pk[nb][mb][i4][1] = pack_bf16x2(d[2], d[3]);
-      }
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          float d[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int row = m0 + acc_row(wm, mb, i4 * 4 + j, lane);
+            float v = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
+            if (row == yrel) v += g;
+            d[j] = row < vc ? v : 0.f;
+          }
+          pk[nb][mb][i4][0] = pack_bf16x2(d[0], d[1]);
+          pk[nb][mb][i4][1] = pack_bf16x2(d[2], d[3]);
+        }
     }
   }
   // The tile leaves through LDS so that both layouts are written with 16-byte coalesced
@@ -413,10 +553,12 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
   const int base = tiles_t * tiles_h;
   const int pid = blockIdx.x;
   if (S == 0 || pid >= base * S) return;   // uniform exit
-  // consecutive hardware ids (different XCDs) take different splits of neighbouring tiles
-  const int split = pid % S;
+  // per-XCD contiguous order, split-major: the workgroups resident on one XCD work on the same
+  // K range of neighbouring tiles and share their operand slices in that XCD's L2
+  const int npid = xcd_regroup(pid, base * S);
+  const int split = npid / base;
   int tt, th;
-  tile_of_index(pid / S, tiles_t, tiles_h, tt, th);
+  tile_of_index(npid % base, tiles_t, tiles_h, tt, th);
   const int m0 = tt * kTile, n0 = th * kTile;
   const int nslices = (vcK + kDK - 1) / kDK;
   const int per = (nslices + S - 1) / S;
@@ -545,11 +687,17 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   }
 
   // ---- forward ----
+  int32_t* fidx = reinterpret_cast<int32_t*>(ws + p.off_fidx);
+  int32_t* nf = reinterpret_cast<int32_t*>(ws + p.off_nf);
+  uint16_t* hf = reinterpret_cast<uint16_t*>(ws + p.off_hc);   // forward use of the gathered-rows buffer
   if (T > 0) {
-    hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(p.tiles_v * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, Hp,
-                       V, T, H, p.tiles_v, tiles_t, p.T_pad, part_m, part_s, part_sz);
-    hipLaunchKernelGGL(k_fused_combine, dim3(unsigned((T + 3) / 4)), dim3(256), 0, s, Wp, Hp, V, T, H, p.tiles_v,
-                       p.T_pad, part_m, part_s, part_sz, targets, logprob, entropy, lse, err_flag);
+    hipLaunchKernelGGL(k_compact_valid, dim3(1), dim3(1024), 0, s, targets, T, p.T_pad, V, fidx, nf, logprob, entropy,
+                       lse, err_flag);
+    hipLaunchKernelGGL(k_gather_rows, dim3(unsigned(p.T_pad / 4)), dim3(256), 0, s, Hp, H, fidx, p.T_pad, hf);
+    hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(p.tiles_v * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hf,
+                       V, H, p.tiles_v, tiles_t, p.T_pad, nf, part_m, part_s, part_sz);
+    hipLaunchKernelGGL(k_fused_combine, dim3(unsigned(p.T_pad / kCombineTokens)), dim3(256), 0, s, Wp, hf, H,
+                       p.tiles_v, p.T_pad, fidx, nf, part_m, part_s, part_sz, targets, logprob, entropy, lse);
   }
   if (!bwd) return launch_status();
 
@@ -578,10 +726,12 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   hipLaunchKernelGGL(k_compact_tokens, dim3(1), dim3(1024), 0, s, g, lse, targets, T, p.T_pad, idx, pos, nact, gc,
                      lsec, yc);
   // hidden rows gathered to hc [T_pad, H] and transposed to hTc, K-slabs over the compacted tokens
-  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.T_pad / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Hp,
+  const bool vec_tr = (H % 8 == 0) && (reinterpret_cast<uintptr_t>(Hp) % 16 == 0) && (reinterpret_cast<uintptr_t>(Wp) % 16 == 0);
+  const auto transpose = vec_tr ? k_gather_transpose_vec : k_gather_transpose;
+  hipLaunchKernelGGL(transpose, dim3(unsigned(p.T_pad / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Hp,
                      int64_t(H), T, H, p.H_pad, idx, p.T_pad, hTc, hc, int64_t(H));
   // weight transposed to WT, K-slabs over the vocabulary; rows V..V_ld of the source do not exist -> zeros
-  hipLaunchKernelGGL(k_gather_transpose, dim3(unsigned(p.V_ld / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Wp,
+  hipLaunchKernelGGL(transpose, dim3(unsigned(p.V_ld / 64), unsigned(p.H_pad / 64)), dim3(256), 0, s, Wp,
                      int64_t(H), int64_t(V), H, p.H_pad, nullptr, int64_t(p.V_ld), WT, nullptr, int64_t(0));
 
   // ---- per vocabulary chunk ----

@@ -87,3 +87,12 @@ def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv,
     torch.cuda.synchronize()
     return dict(loss=loss, clip_frac=clip, logprob=lp_out, dlogits=dl, err=int(err.item()), entropy=ent_out,
                 lse=lse_out)
+
+
+def loss_bound(loss_ref, loss_terms):
+    """Allowed |loss - loss_ref|: 1e-4 relative, plus fp32 rounding relative to the sum of the
+    per-token magnitudes.  With group-standardised advantages (Eq. 1) the per-token terms of
+    Eq. 2 cancel almost exactly when the ratio is near 1, so the total can be orders of magnitude
+    smaller than its terms; each term carries the fp32 rounding of its log-probability (an ulp
+    of a value near 10 is about 1e-6), and that error does not shrink with the total."""
+    return 1e-4 * abs(float(loss_ref)) + 2.0 ** -22 * float(np.abs(np.asarray(loss_terms, np.float64)).sum())

@@ -2,7 +2,7 @@
 the gradients w.r.t. hidden states and LM-head weight, against the float64 checker (which
 forms the logits as a float64 product and then applies the logits-path definitions).
 
-Tolerances: log-prob / entropy / lse 2e-3 absolute; loss 1e-4 relative; gradients are checked
+Tolerances: log-prob / entropy / lse 2e-3 absolute; loss 1e-4 relative (plus fp32 rounding of the cancelling terms, see loss_bound); gradients are checked
 scale-free, per row, against 1e-2 of the largest reference entry of that row (dz is rounded
 to bf16 before it enters the two gradient contractions, dhidden is stored in bf16)."""
 import numpy as np
@@ -94,7 +94,7 @@ def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, 
     out = run_fused(gh, wl, h, W, wl.targets, bwd=dict(old=old, adv=a32, weight=w32, grad_scale=grad_scale),
                     dweight_dtype=dweight_dtype)
     assert out["err"] == 0
-    assert abs(out["loss"].item() - ref["loss"]) <= 1e-4 * abs(ref["loss"]) + 1e-12
+    assert abs(out["loss"].item() - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"])
     assert abs(out["clip_frac"].item() - ref["clip_frac"]) < 1e-6
     dh = out["dhidden"].float().cpu().numpy().astype(np.float64)
     dw = out["dweight"].float().cpu().numpy().astype(np.float64)
