@@ -246,10 +246,45 @@ __global__ __launch_bounds__(NT) void k_dlogits(
 }
 
 // Long aligned rows: one 16-byte vector per thread, (row, segment) per workgroup.  Workgroups
-// are tiny and start in address order, so the whole GPU sweeps the tensor as one linear stream
-// of reads and one of writes; measured 6.4 TB/s against 5.2 TB/s for a workgroup that loops
-// over its row.
-constexpr int kSegNT = 512;
+// are small and start in address order, so the whole GPU sweeps the tensor as one linear stream
+// of reads and one of writes (a workgroup that loops over its row reaches 5.2 TB/s, this form
+// 5.7; two or four vectors per thread were 8 % slower, 512 and 1024 threads 1-2 % slower).  The
+// vector load is issued as soon as g_t is known, ahead of the other per-row scalars: with
+// one load per thread every dependent scalar fetch in front of it costs throughput (7 % here).
+constexpr int kSegNT = 256;
+constexpr int kSegVPT = 1;
+constexpr int kSegVecs = kSegNT * kSegVPT;   // vectors per segment
+
+template <bool BF16>
+__device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, float g, float ng, float c) {
+  u32x4_t o;
+  if constexpr (BF16) {
+    float z[8], d[8];
+    unpack8(v, z);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
+    if (k == (y >> 3)) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
+    }
+    o.x = pack_bf16x2(d[0], d[1]);
+    o.y = pack_bf16x2(d[2], d[3]);
+    o.z = pack_bf16x2(d[4], d[5]);
+    o.w = pack_bf16x2(d[6], d[7]);
+  } else {
+    float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) d[e] = ng * exp2_fast(fmaf(d[e], kLog2e, c));
+    if (k == (y >> 2)) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) d[e] += (e == (y & 3)) ? g : 0.f;
+    }
+    o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
+    o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
+  }
+  return o;
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
     const void* logits, int V, int64_t ld, int segs, const int32_t* __restrict__ targets,
@@ -263,48 +298,30 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
   const char* zrow = reinterpret_cast<const char*>(logits) + row_off;
   char* drow = reinterpret_cast<char*>(dlogits) + row_off;
   const int nvec = V / E;
-  const int k = seg * kSegNT + threadIdx.x;
+  const int k0 = seg * kSegVecs + threadIdx.x;
   const int j = nvec * E + threadIdx.x;          // ragged tail, done by segment 0
   const bool tail = seg == 0 && j < V;
   if (g == 0.f) {   // uniform over the workgroup: nothing to read
-    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < kSegVPT; ++i)
+      if (k0 + i * kSegNT < nvec) reinterpret_cast<u32x4_t*>(drow)[k0 + i * kSegNT] = u32x4_t{0u, 0u, 0u, 0u};
     if (tail) {
       if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
       else reinterpret_cast<float*>(drow)[j] = 0.f;
     }
     return;
   }
+  u32x4_t v[kSegVPT];
+#pragma unroll
+  for (int i = 0; i < kSegVPT; ++i)
+    if (k0 + i * kSegNT < nvec) v[i] = reinterpret_cast<const u32x4_t*>(zrow)[k0 + i * kSegNT];
   const int y = targets[t];
   const float c = -lse[t] * kLog2e;
   const float ng = -g;
-  if (k < nvec) {
-    const u32x4_t v = reinterpret_cast<const u32x4_t*>(zrow)[k];
-    u32x4_t o;
-    if constexpr (BF16) {
-      float z[8], d[8];
-      unpack8(v, z);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
-      if (k == (y >> 3)) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
-      }
-      o.x = pack_bf16x2(d[0], d[1]);
-      o.y = pack_bf16x2(d[2], d[3]);
-      o.z = pack_bf16x2(d[4], d[5]);
-      o.w = pack_bf16x2(d[6], d[7]);
-    } else {
-      float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) d[e] = ng * exp2_fast(fmaf(d[e], kLog2e, c));
-      if (k == (y >> 2)) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) d[e] += (e == (y & 3)) ? g : 0.f;
-      }
-      o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
-      o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
-    }
-    reinterpret_cast<u32x4_t*>(drow)[k] = o;
+  for (int i = 0; i < kSegVPT; ++i) {
+    const int k = k0 + i * kSegNT;
+    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = dlogits_vec<BF16>(v[i], k, y, g, ng, c);
   }
   if (tail) {
     if constexpr (BF16) {
@@ -326,7 +343,7 @@ static void dispatch_dlogits(const void* logits, int64_t T, int V, int64_t ld, c
   const int per_vec = VEC ? (BF16 ? 8 : 4) : 1;
   const int64_t work = (V + per_vec - 1) / per_vec;
   if constexpr (VEC) {
-    const int64_t segs = (V / per_vec + kSegNT - 1) / kSegNT;
+    const int64_t segs = (V / per_vec + kSegVecs - 1) / kSegVecs;
     if (work > 16 * 256 && T * segs < (int64_t(1) << 31)) {
       hipLaunchKernelGGL((k_dlogits_seg<BF16>), dim3(unsigned(T * segs)), dim3(kSegNT), 0, s, logits, V, ld, int(segs),
                          targets, lse, g, dlogits);
