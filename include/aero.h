@@ -167,7 +167,14 @@ aero_status aero_grpo_loss_bwd(
  * Backward part (old_logprob .. dweight; pass old_logprob == NULL for forward only):
  *   loss f32[1]; dhidden bf16 [T, H] = dz @ weight; dweight [V, H] = dz^T @ hidden in
  *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd.
- * workspace: aero_workspace_bytes(AERO_OP_LMHEAD_FUSED, T, V, H, R, 0).
+ * Rows whose target is negative take no part in the contraction (their outputs are 0); a
+ * target >= V is treated the same way and raises AERO_DERR_BAD_TARGET in err_flag.
+ * workspace: aero_workspace_bytes(AERO_OP_LMHEAD_FUSED, T, V, H, R, 0) bytes of device memory,
+ * 256-byte aligned, owned by the caller, contents undefined before and after the call.
+ * Errors: AERO_ERR_SHAPE (T < 0, V < 1 or > 2^24, H < 8, H % 8 != 0, or a padded backward
+ * operand of 4 GiB or more: H, T or the vocabulary chunk too large for 32-bit offsets),
+ * AERO_ERR_DTYPE (dweight_dtype), AERO_ERR_NULL, AERO_ERR_ALIGN, AERO_ERR_WORKSPACE,
+ * AERO_ERR_HIP (launch failure).  Asynchronous on `stream`; nothing is allocated.
  */
 aero_status aero_lmhead_logprob_fused(
     const void* hidden, const void* weight, int64_t T, int32_t H, int32_t V,

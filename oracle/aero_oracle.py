@@ -225,10 +225,18 @@ def token_terms(lp: float, lp_old: float, A: float, w: float, eps_lo: float, eps
     return -w * s, g, unclipped, rho
 
 
+def entropy_grad_row(z: np.ndarray, lse: float, ent: float) -> np.ndarray:
+    """d H / d z_j for a softmax policy with H = - sum_j pi_j ln pi_j:
+    d pi_k / d z_j = pi_k (1[k = j] - pi_j), hence  d H / d z_j = - pi_j (ln pi_j + H),
+    with ln pi_j = z_j - lse."""
+    lnp = z - lse
+    return -np.exp(lnp) * (lnp + ent)
+
+
 def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old_logprob,
                   token_rollout, adv, weight, eps_lo: float, eps_hi: float,
                   grad_scale: float = 1.0, want_dlogits: bool = True,
-                  z64: Optional[np.ndarray] = None):
+                  z64: Optional[np.ndarray] = None, entropy_coef: float = 0.0):
     """loss = - sum_t w_{i(t)} s_t over tokens of kept rollouts, and dlogits.
 
     A row contributes nothing, and its gradient row is exactly +0, when it is padding
@@ -238,6 +246,12 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
     because d log pi(y) / d z_j = 1[j = y] - pi_j for a softmax policy.
     clip_frac = clipped tokens / tokens with a non-zero advantage.
 
+    Entropy bonus (Table 8 gives a coefficient only; aggregation taken to be that of Eq. 2):
+    with entropy_coef = c != 0 the objective gains  c sum_t w_{i(t)} H_t  over every token of a
+    rollout with w != 0 (whatever its advantage, clipped or not), so
+    loss -= c w H_t  and  dlogits[t, j] += - grad_scale c w dH_t/dz_j
+                                         = grad_scale c w pi_j (ln pi_j + H_t).
+
     ``z64`` may supply the logits already in float64 ([T, V]) instead of ``logits``.
     """
     T = len(targets)
@@ -245,29 +259,37 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
     weight = np.asarray(weight, np.float64)
     old_logprob = np.asarray(old_logprob, np.float64)
     eps_lo, eps_hi, grad_scale = float(eps_lo), float(eps_hi), float(grad_scale)
+    c_ent = float(entropy_coef)
     loss = 0.0
     g = np.zeros(T)
+    e = np.zeros(T)
     lp = np.zeros(T)
     loss_terms = np.zeros(T)
     dz = np.zeros((T, V)) if want_dlogits else None
     n_signal = n_clipped = 0
     for t in range(T):
         i, y = int(token_rollout[t]), int(targets[t])
-        if i < 0 or y < 0 or adv[i] == 0.0 or weight[i] == 0.0:
+        if i < 0 or y < 0 or weight[i] == 0.0 or (adv[i] == 0.0 and c_ent == 0.0):
             continue
         z = z64[t] if z64 is not None else widen(logits[t, :V], dtype)
-        lp[t], _, lse = logprob_row(z, y)
-        loss_terms[t], g[t], unclipped, _ = token_terms(lp[t], old_logprob[t], adv[i], weight[i],
-                                                        eps_lo, eps_hi, grad_scale)
+        lp[t], ent, lse = logprob_row(z, y)
+        if adv[i] != 0.0:
+            loss_terms[t], g[t], unclipped, _ = token_terms(lp[t], old_logprob[t], adv[i], weight[i],
+                                                            eps_lo, eps_hi, grad_scale)
+            n_signal += 1
+            n_clipped += 0 if unclipped else 1
+        if c_ent != 0.0:
+            loss_terms[t] -= c_ent * weight[i] * ent
+            e[t] = grad_scale * c_ent * weight[i]
         loss += loss_terms[t]
-        n_signal += 1
-        n_clipped += 0 if unclipped else 1
-        if want_dlogits and g[t] != 0.0:
+        if want_dlogits and (g[t] != 0.0 or e[t] != 0.0):
             row = -g[t] * np.exp(z - lse)
             row[y] += g[t]
+            if e[t] != 0.0:
+                row -= e[t] * entropy_grad_row(z, lse, ent)
             dz[t] = row
     clip_frac = n_clipped / n_signal if n_signal else 0.0
-    return dict(loss=loss, clip_frac=clip_frac, logprob=lp, g=g, loss_terms=loss_terms, dlogits=dz)
+    return dict(loss=loss, clip_frac=clip_frac, logprob=lp, g=g, e=e, loss_terms=loss_terms, dlogits=dz)
 
 
 # ------------------------------------------------------------------------------------------
@@ -280,7 +302,7 @@ def lmhead_logits(hidden_bits: np.ndarray, weight_bits: np.ndarray) -> np.ndarra
 
 
 def lmhead_fused(hidden_bits, weight_bits, targets, old_logprob=None, token_rollout=None,
-                 adv=None, weight=None, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0):
+                 adv=None, weight=None, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0, entropy_coef=0.0):
     """Forward statistics of the product logits and, when the loss inputs are given, the
     loss and the gradients dhidden = dz W and dweight = dz^T h with the unrounded dz."""
     z = lmhead_logits(hidden_bits, weight_bits)
@@ -294,9 +316,9 @@ def lmhead_fused(hidden_bits, weight_bits, targets, old_logprob=None, token_roll
     out = dict(logprob=lp, entropy=ent, lse=lse)
     if old_logprob is not None:
         b = grpo_loss_bwd(None, "f64", V, targets, old_logprob, token_rollout, adv, weight,
-                          eps_lo, eps_hi, grad_scale, want_dlogits=True, z64=z)
+                          eps_lo, eps_hi, grad_scale, want_dlogits=True, z64=z, entropy_coef=entropy_coef)
         dz = b["dlogits"]
-        out.update(loss=b["loss"], clip_frac=b["clip_frac"], g=b["g"], loss_terms=b["loss_terms"],
+        out.update(loss=b["loss"], clip_frac=b["clip_frac"], g=b["g"], e=b["e"], loss_terms=b["loss_terms"],
                    dhidden=dz @ widen(weight_bits, "bf16"),
                    dweight=dz.T @ widen(hidden_bits, "bf16"))
     return out

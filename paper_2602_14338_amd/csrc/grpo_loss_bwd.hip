@@ -14,7 +14,7 @@ aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int
                                const int32_t* targets, const uint8_t* row_active, float* logprob,
                                float* entropy, float* lse, int32_t* err_flag, hipStream_t s);
 bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits, const void* dlogits);
-void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
+aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
@@ -402,9 +402,10 @@ extern "C" aero_status aero_grpo_loss_bwd(
     // statistics are computed here; with entropy_out / lse_out they cover every valid row
     const int stats_all = (entropy_out || lse_out) ? 1 : 0;
     if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
-      single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                         grad_scale, stats_all, ws.g, ws.loss_term, ws.flag, logprob_out, entropy_out, lse_out,
-                         dlogits, err_flag, ws.counter, s);
+      const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
+                                                eps_lo, eps_hi, grad_scale, stats_all, ws.g, ws.loss_term, ws.flag,
+                                                logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter, s);
+      if (sp != AERO_OK) return sp;
       hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
       return launch_status();
     }

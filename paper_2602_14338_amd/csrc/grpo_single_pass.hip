@@ -4,6 +4,8 @@
 // log-partition is reduced across the workgroup, and the gradient row is produced from the
 // registers - 4 bytes of traffic per logit instead of 6 for a forward pass followed by a
 // backward pass.
+#include <mutex>
+
 #include "aero_device.h"
 
 namespace aero {
@@ -420,7 +422,7 @@ bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits
          reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0;
 }
 
-void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
+aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
@@ -434,12 +436,14 @@ void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const 
   else {
     constexpr int NL = 9;
     constexpr int kLdsBytes = NL * kSpNT * 16;   // 144 KB of wave-private slots
-    static bool attr_done = false;
-    if (!attr_done) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_row_stream<20, NL>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-      attr_done = true;
-    }
+    // raising the dynamic-LDS limit is per function; done once per process, safely from any thread
+    static std::once_flag attr_once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(attr_once, [] {
+      attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(k_row_stream<20, NL>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    });
+    if (attr_rc != hipSuccess) return AERO_ERR_HIP;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {
       int n = 0;
@@ -451,6 +455,7 @@ void single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const 
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
                        logprob_out, entropy_out, lse_out, dz, err_flag, row_counter);
   }
+  return AERO_OK;
 }
 
 }  // namespace aero

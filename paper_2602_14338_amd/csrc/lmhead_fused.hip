@@ -19,6 +19,8 @@
 //           k_gemm_dw         dweight[chunk rows] = dz_chunk^T @ hidden     (complete per chunk)
 //           k_scatter_dh      fp32 partials summed in fixed order -> bf16 dhidden at the original rows
 // All contractions use the same 256 x 256 x 64 MFMA tile with both operands K-contiguous.
+#include <mutex>
+
 #include "gemm_tile.h"
 
 namespace aero {
@@ -664,6 +666,11 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     return AERO_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(hidden) % 16 || reinterpret_cast<uintptr_t>(weight) % 16) return AERO_ERR_ALIGN;
   const FusedPlan p = make_plan(T, V, H);
+  // operands are addressed with 32-bit byte offsets: every slab operand must stay below 4 GiB
+  constexpr size_t kOperandLimit = size_t(1) << 32;
+  if (size_t(p.H_pad) * size_t(p.T_pad) * 2 >= kOperandLimit || size_t(p.H_pad) * size_t(p.VC) * 2 >= kOperandLimit ||
+      size_t(p.T_pad) * size_t(p.VC) * 2 >= kOperandLimit)
+    return AERO_ERR_SHAPE;
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kWsAlign || workspace_bytes < p.total)
     return AERO_ERR_WORKSPACE;
   hipStream_t s = as_stream(stream);
@@ -675,16 +682,18 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   float* part_sz = part_s + size_t(p.tiles_v) * p.T_pad;
   const int tiles_t = int(p.T_pad / kTile);
 
-  static bool attr_done = false;   // raising the dynamic-LDS limit is per function, once per process
-  if (!attr_done) {
+  // raising the dynamic-LDS limit is per function; done once per process, safely from any thread
+  static std::once_flag attr_once;
+  static aero_status attr_rc = AERO_OK;
+  std::call_once(attr_once, [] {
     if (set_lds(reinterpret_cast<const void*>(k_fused_stats)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_fused_dz), kDzLdsBytes) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dh)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<true>)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<false>)) != AERO_OK)
-      return AERO_ERR_HIP;
-    attr_done = true;
-  }
+      attr_rc = AERO_ERR_HIP;
+  });
+  if (attr_rc != AERO_OK) return attr_rc;
 
   // ---- forward ----
   int32_t* fidx = reinterpret_cast<int32_t*>(ws + p.off_fidx);

@@ -366,6 +366,77 @@ def test_gradient_matches_central_differences_and_all_clip_cases_occur():
     assert len(seen) == 6
 
 
+# ------------------------------------------------------------------ entropy bonus (Table 8)
+
+def torch_loss_with_entropy(z, y, tr, adv, w, old, eps_lo, eps_hi, c_ent):
+    """Eq. 2 minus c * sum_t w_t H_t, H from torch's own softmax; autograd gives the gradient.
+    Rollouts with weight 0 are outside both sums."""
+    zt = torch.tensor(z, dtype=torch.float64, requires_grad=True)
+    logp = torch.log_softmax(zt, dim=1)
+    lp = logp.gather(1, torch.tensor(y, dtype=torch.int64)[:, None])[:, 0]
+    rho = torch.exp(lp - torch.tensor(old))
+    A = torch.tensor(adv)[torch.tensor(tr, dtype=torch.int64)]
+    W = torch.tensor(w)[torch.tensor(tr, dtype=torch.int64)]
+    s = torch.minimum(rho * A, torch.clamp(rho, 1 - eps_lo, 1 + eps_hi) * A)
+    H = torch.distributions.Categorical(logits=zt).entropy()
+    loss = -(W * s).sum() - c_ent * (W * H).sum()
+    loss.backward()
+    return loss.item(), zt.grad.numpy()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_entropy_bonus_matches_autograd(seed):
+    z, y, tr, adv, w, old = tiny_problem(200 + seed)
+    w[1] = 0.0                                    # a dropped rollout: no loss, no entropy term
+    for c_ent, gs in ((1e-3, 1.0), (0.5, 4.0)):
+        out = orc.grpo_loss_bwd(None, "f64", z.shape[1], y, old, tr, adv, w, 0.2, 0.2, grad_scale=gs, z64=z,
+                                entropy_coef=c_ent)
+        loss, grad = torch_loss_with_entropy(z, y, tr, adv, w, old, 0.2, 0.2, c_ent)
+        assert abs(out["loss"] - loss) < 1e-13
+        assert np.allclose(out["dlogits"], gs * grad, rtol=1e-10, atol=1e-15)
+        assert not out["dlogits"][tr == 1].any()
+        # rollout 0 has advantage 0: only the entropy term reaches its rows
+        assert out["dlogits"][tr == 0].any() and not out["g"][tr == 0].any()
+        assert np.abs(out["dlogits"].sum(axis=1)).max() < 1e-15     # rows still sum to zero
+
+
+def test_entropy_gradient_closed_forms_and_central_differences():
+    V = 7
+    # uniform policy: H = ln V is the maximum, its gradient vanishes
+    z = np.full(V, 0.3)
+    _, ent, lse = orc.logprob_row(z, 0)
+    assert abs(ent - math.log(V)) < 1e-15
+    assert np.abs(orc.entropy_grad_row(z, lse, ent)).max() < 1e-16
+    # two-point policy (p, 1-p): H = -p ln p - q ln q, dH/dz_0 = p q ln(q / p)
+    for p in (0.1, 0.5, 0.9):
+        z2 = np.array([math.log(p), math.log(1 - p)])
+        _, ent2, lse2 = orc.logprob_row(z2, 0)
+        g2 = orc.entropy_grad_row(z2, lse2, ent2)
+        assert abs(g2[0] - p * (1 - p) * math.log((1 - p) / p)) < 1e-15 and abs(g2.sum()) < 1e-16
+    rng = np.random.default_rng(5)
+    z = rng.normal(0, 2, size=V)
+    _, ent, lse = orc.logprob_row(z, 0)
+    an = orc.entropy_grad_row(z, lse, ent)
+    h = 1e-6
+    for j in range(V):
+        zp, zm = z.copy(), z.copy()
+        zp[j] += h
+        zm[j] -= h
+        fd = (orc.logprob_row(zp, 0)[1] - orc.logprob_row(zm, 0)[1]) / (2 * h)
+        assert abs(an[j] - fd) < 1e-9
+    # through the whole loss: with rho = 1 and all advantages 0 the loss is - c sum_t w_t H_t
+    T, R = 6, 2
+    zz = rng.normal(0, 1.5, size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    tr = (np.arange(T) % R).astype(np.int32)
+    w = np.array([0.25, 0.125])
+    lp = np.array([orc.logprob_row(zz[t], y[t])[0] for t in range(T)])
+    out = orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(R), w, 0.2, 0.2, z64=zz, entropy_coef=0.01)
+    H = np.array([orc.logprob_row(zz[t], y[t])[1] for t in range(T)])
+    assert abs(out["loss"] + 0.01 * (w[tr] * H).sum()) < 1e-16 and out["clip_frac"] == 0.0
+    assert not orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(R), w, 0.2, 0.2, z64=zz)["dlogits"].any()
+
+
 def test_clip_edge_counts_as_unclipped():
     for A, lp_minus_old in ((1.0, math.log(1.2)), (-1.0, math.log(0.8))):
         rho = math.exp(lp_minus_old)
