@@ -130,13 +130,21 @@ aero_status aero_logprob_fwd(
  *            (A > 0: rho <= 1 + eps_hi;  A < 0: rho >= 1 - eps_lo), else 0
  *     dlogits[t, j] = g_t * (1[j == targets[t]] - exp(z[t,j] - lse[t]))
  *   every other row (padding, ignored, A == 0, w == 0, clipped): dlogits row = +0.
+ * Entropy bonus (Table 8 lists a coefficient; it is aggregated with Eq. 2's weights): with
+ * entropy_coef = c != 0 every token of a rollout with w != 0, whatever A or the clip decision,
+ *     loss -= c * w * H_t,   dlogits[t, j] += grad_scale * c * w * p_j * (ln p_j + H_t),
+ *     p_j = exp(z[t,j] - lse[t]), H_t = entropy of row t.
+ * With c != 0 the statistics-and-gradient call is two passes over HBM (6 bytes per logit).
  *
  * logits / dlogits  [T, ld], same dtype and ld; dlogits may alias logits (in place).
  * lse      f32[T] from aero_logprob_fwd, or NULL: then the statistics are computed here.  With
  *          lse == NULL, bf16 logits, 16-byte aligned rows and 8192 <= V <= 163840 the whole call
  *          is one pass over HBM (the row is held in registers: 4 bytes of traffic per logit);
  *          otherwise a forward pass into the workspace precedes the gradient pass.
+ * entropy  f32[T] from aero_logprob_fwd; read only when lse != NULL and entropy_coef != 0
+ *          (AERO_ERR_NULL if missing then), may be NULL otherwise.
  * old_logprob f32[T]; token_rollout i32[T] (-1 = padding); adv, weight f32[R].
+ * entropy_coef  c above; 0 switches the term off (NaN: AERO_ERR_SHAPE).
  * Outputs  loss f32[1] (deterministic: fixed-order reduction); clip_frac f32[1] or NULL
  *          (clipped tokens / tokens with A != 0 and w != 0); dlogits or NULL (loss only);
  *          logprob_out f32[T] or NULL: current log-prob of the tokens that carry signal, 0 elsewhere;
@@ -148,10 +156,10 @@ aero_status aero_logprob_fwd(
  */
 aero_status aero_grpo_loss_bwd(
     const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld,
-    const int32_t* targets, const float* lse /*nullable*/,
+    const int32_t* targets, const float* lse /*nullable*/, const float* entropy /*nullable*/,
     const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight, int32_t R,
-    float eps_lo, float eps_hi, float grad_scale,
+    float eps_lo, float eps_hi, float grad_scale, float entropy_coef,
     float* loss, float* clip_frac /*nullable*/, float* logprob_out /*nullable*/,
     float* entropy_out /*nullable*/, float* lse_out /*nullable*/,
     void* dlogits /*nullable*/, int32_t* err_flag /*nullable*/,
@@ -166,7 +174,9 @@ aero_status aero_grpo_loss_bwd(
  * Forward outputs  logprob[T], lse[T] f32, entropy[T] f32 or NULL.
  * Backward part (old_logprob .. dweight; pass old_logprob == NULL for forward only):
  *   loss f32[1]; dhidden bf16 [T, H] = dz @ weight; dweight [V, H] = dz^T @ hidden in
- *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd.
+ *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd
+ *   (entropy_coef included: the entropy of the forward part is used, also when the
+ *   `entropy` output is NULL).
  * Rows whose target is negative take no part in the contraction (their outputs are 0); a
  * target >= V is treated the same way and raises AERO_DERR_BAD_TARGET in err_flag.
  * workspace: aero_workspace_bytes(AERO_OP_LMHEAD_FUSED, T, V, H, R, 0) bytes of device memory,
@@ -182,7 +192,7 @@ aero_status aero_lmhead_logprob_fused(
     float* logprob, float* entropy /*nullable*/, float* lse,
     const float* old_logprob /*nullable => forward only*/, const int32_t* token_rollout,
     const float* adv, const float* weight_rollout, int32_t R,
-    float eps_lo, float eps_hi, float grad_scale,
+    float eps_lo, float eps_hi, float grad_scale, float entropy_coef,
     float* loss, float* clip_frac /*nullable*/, void* dhidden, void* dweight, int32_t dweight_dtype,
     int32_t* err_flag /*nullable*/,
     void* workspace, size_t workspace_bytes, void* stream);

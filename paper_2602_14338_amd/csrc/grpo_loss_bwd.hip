@@ -6,6 +6,11 @@
 //   loss reduce  one workgroup, fixed summation order (bitwise reproducible), fp64 accumulator
 //   dlogits      one workgroup per row: dz = g_t (onehot - exp(z - lse)); rows with g_t == 0
 //                are not read, they are only filled with +0
+// Entropy bonus (Table 8 lists a coefficient; aggregated here with Eq. 2's weights): with a
+// coefficient c != 0 every token of a rollout with w != 0 also contributes -c w H_t to the loss
+// and e_t pi_j (ln pi_j + H_t), e_t = grad_scale c w, to its gradient row.  A row is then
+// dz_j = pi_j (a z_j + b) + g 1[j = y]  with a = e_t, b = e_t (H_t - lse_t) - g_t, and the
+// kernels with ENT = true read (a, b) per row; with c == 0 the ENT = false kernels run.
 #include "aero_device.h"
 
 namespace aero {
@@ -28,31 +33,36 @@ struct LossWorkspace {
   float* lse;        // [T] used when the caller gives none
   float* lp_tmp;     // [T] sink for the forward pass's log-prob when lse is recomputed
   uint8_t* signal;   // [T] rows that carry signal, so the recomputing forward pass skips the rest
+  float* ea;         // [T] entropy bonus: a_t = grad_scale c w
+  float* eb;         // [T] entropy bonus: b_t = a_t (H_t - lse_t) - g_t
+  float* ent;        // [T] entropy of the rows when the caller passes no array for it
   int32_t* counter;  // [1] row counter of the streaming single-pass kernel
 };
 constexpr size_t kAlign = 256;
 inline size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
-size_t loss_workspace_bytes(int64_t T) { return 6 * seg(T) + kAlign; }
+size_t loss_workspace_bytes(int64_t T) { return 9 * seg(T) + kAlign; }
 inline LossWorkspace carve(void* ws, int64_t T) {
   char* p = reinterpret_cast<char*>(ws);
   const size_t s = seg(T);
   return LossWorkspace{reinterpret_cast<float*>(p), reinterpret_cast<float*>(p + s),
                        reinterpret_cast<int32_t*>(p + 2 * s), reinterpret_cast<float*>(p + 3 * s),
                        reinterpret_cast<float*>(p + 4 * s), reinterpret_cast<uint8_t*>(p + 5 * s),
-                       reinterpret_cast<int32_t*>(p + 6 * s)};
+                       reinterpret_cast<float*>(p + 6 * s), reinterpret_cast<float*>(p + 7 * s),
+                       reinterpret_cast<float*>(p + 8 * s), reinterpret_cast<int32_t*>(p + 9 * s)};
 }
 
 // ---------------------------------------------------------------- which rows carry signal
-// stats_all: every valid row (rollout index and sampled token in range) needs statistics
+// stats_all: every valid row (rollout index and sampled token in range) needs statistics;
+// every_weighted: rows of rollouts with advantage 0 count too (entropy bonus)
 __global__ __launch_bounds__(256) void k_signal_mask(
     int64_t T, int V, const int32_t* __restrict__ targets, const int32_t* __restrict__ token_rollout,
-    const float* __restrict__ adv, const float* __restrict__ weight, int R, int stats_all,
+    const float* __restrict__ adv, const float* __restrict__ weight, int R, int stats_all, int every_weighted,
     uint8_t* __restrict__ signal) {
   const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
   if (t >= T) return;
   const int i = token_rollout[t], y = targets[t];
   const bool valid = i >= 0 && i < R && y >= 0 && y < V;
-  signal[t] = (valid && (stats_all || (adv[i] != 0.f && weight[i] != 0.f))) ? 1 : 0;
+  signal[t] = (valid && (stats_all || (weight[i] != 0.f && (every_weighted || adv[i] != 0.f)))) ? 1 : 0;
 }
 
 // ---------------------------------------------------------------- token terms
@@ -64,20 +74,21 @@ __global__ __launch_bounds__(256) void k_token_terms(
     const float* __restrict__ lse, const float* __restrict__ logprob_in,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R,
-    float eps_lo, float eps_hi, float grad_scale,
+    float eps_lo, float eps_hi, float grad_scale, float ent_coef, const float* __restrict__ entropy,
     float* __restrict__ g_out, float* __restrict__ term_out, int32_t* __restrict__ flag_out,
+    float* __restrict__ ea_out, float* __restrict__ eb_out,
     float* __restrict__ logprob_out, int32_t* __restrict__ err_flag) {
   const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
   if (t >= T) return;
   const int i = token_rollout[t];
   const int y = targets[t];
-  float g = 0.f, term = 0.f, lp = 0.f;
+  float g = 0.f, term = 0.f, lp = 0.f, ea = 0.f, eb = 0.f;
   int flag = 0;
   if (i >= R || y >= V) {
     if (err_flag) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
   } else if (i >= 0 && y >= 0) {
     const float A = adv[i], w = weight[i];
-    if (A != 0.f && w != 0.f) {   // decided before the ratio is touched
+    if (w != 0.f && (A != 0.f || ent_coef != 0.f)) {   // decided before the ratio is touched
       if constexpr (LP_GIVEN) {
         lp = logprob_in[t];
       } else {
@@ -86,19 +97,31 @@ __global__ __launch_bounds__(256) void k_token_terms(
         else zy = reinterpret_cast<const float*>(logits)[size_t(t) * size_t(ld) + y];
         lp = zy - lse[t];
       }
-      const float rho = expf(lp - old_logprob[t]);
-      const float lo = 1.f - eps_lo, hi = 1.f + eps_hi;
-      const float clipped = fminf(fmaxf(rho, lo), hi);
-      const float s = fminf(rho * A, clipped * A);
-      const bool unclipped = A > 0.f ? (rho <= hi) : (rho >= lo);
-      term = -w * s;
-      g = unclipped ? -grad_scale * w * A * rho : 0.f;
-      flag = unclipped ? 1 : 2;
+      if (A != 0.f) {
+        const float rho = expf(lp - old_logprob[t]);
+        const float lo = 1.f - eps_lo, hi = 1.f + eps_hi;
+        const float clipped = fminf(fmaxf(rho, lo), hi);
+        const float s = fminf(rho * A, clipped * A);
+        const bool unclipped = A > 0.f ? (rho <= hi) : (rho >= lo);
+        term = -w * s;
+        g = unclipped ? -grad_scale * w * A * rho : 0.f;
+        flag = unclipped ? 1 : 2;
+      }
+      if (ent_coef != 0.f) {
+        const float H = entropy[t];
+        term -= ent_coef * w * H;
+        ea = grad_scale * ent_coef * w;
+        eb = ea * (H - lse[t]) - g;
+      }
     }
   }
   g_out[t] = g;
   term_out[t] = term;
   flag_out[t] = flag;
+  if (ea_out) {
+    ea_out[t] = ea;
+    eb_out[t] = eb;
+  }
   if (logprob_out) logprob_out[t] = lp;
 }
 
@@ -136,12 +159,16 @@ __global__ __launch_bounds__(kReduceNT) void k_loss_reduce(
 }
 
 // ---------------------------------------------------------------- dlogits
-template <int NT, bool BF16, bool VEC>
+// ENT: the row also carries the entropy-bonus term, dz_j = pi_j (a z_j + b) + g 1[j = y].
+template <int NT, bool BF16, bool VEC, bool ENT>
 __global__ __launch_bounds__(NT) void k_dlogits(
     const void* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
-    const float* __restrict__ lse, const float* __restrict__ g_arr, void* dlogits) {
+    const float* __restrict__ lse, const float* __restrict__ g_arr, const float* __restrict__ ea,
+    const float* __restrict__ eb, void* dlogits) {
   const int64_t t = blockIdx.x;
   const float g = g_arr[t];
+  float a = 0.f;
+  if constexpr (ENT) a = ea[t];
   constexpr size_t kEltBytes = BF16 ? 2 : 4;
   constexpr int E = BF16 ? 8 : 4;
   const size_t row_off = size_t(t) * size_t(ld) * kEltBytes;
@@ -149,7 +176,7 @@ __global__ __launch_bounds__(NT) void k_dlogits(
   char* drow = reinterpret_cast<char*>(dlogits) + row_off;
   const int tid = threadIdx.x;
 
-  if (g == 0.f) {   // uniform over the workgroup: nothing to read
+  if (g == 0.f && a == 0.f) {   // uniform over the workgroup: nothing to read
     if constexpr (VEC) {
       u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
       const int nvec = V / E;
@@ -172,9 +199,12 @@ __global__ __launch_bounds__(NT) void k_dlogits(
   const int y = targets[t];
   const float c = -lse[t] * kLog2e;
   const float ng = -g;
-  // dz_j = -g * exp(z_j - lse) (+ g at the sampled token)
+  float b = ng;
+  if constexpr (ENT) b = eb[t];
+  // dz_j = -g * exp(z_j - lse) (+ g at the sampled token); with the entropy term (a z_j + b) replaces -g
+  auto scale = [&](float z) -> float { return ENT ? fmaf(a, z, b) : ng; };
   auto grad = [&](float z, int j) -> float {
-    float d = ng * exp2_fast(fmaf(z, kLog2e, c));
+    float d = scale(z) * exp2_fast(fmaf(z, kLog2e, c));
     return j == y ? d + g : d;
   };
   if constexpr (VEC) {
@@ -190,7 +220,7 @@ __global__ __launch_bounds__(NT) void k_dlogits(
         unpack8(v, z);
         float d[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) d[k] = ng * exp2_fast(fmaf(z[k], kLog2e, c));
+        for (int k = 0; k < 8; ++k) d[k] = scale(z[k]) * exp2_fast(fmaf(z[k], kLog2e, c));
         if (i == yvec) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) d[k] += (k == (y & 7)) ? g : 0.f;
@@ -202,7 +232,7 @@ __global__ __launch_bounds__(NT) void k_dlogits(
       } else {
         float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) d[k] = ng * exp2_fast(fmaf(d[k], kLog2e, c));
+        for (int k = 0; k < 4; ++k) d[k] = scale(d[k]) * exp2_fast(fmaf(d[k], kLog2e, c));
         if (i == yvec) {
 #pragma unroll
           for (int k = 0; k < 4; ++k) d[k] += (k == (y & 3)) ? g : 0.f;
@@ -255,14 +285,15 @@ constexpr int kSegNT = 256;
 constexpr int kSegVPT = 1;
 constexpr int kSegVecs = kSegNT * kSegVPT;   // vectors per segment
 
-template <bool BF16>
-__device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, float g, float ng, float c) {
+template <bool BF16, bool ENT>
+__device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, float g, float a, float b, float c) {
+  auto scale = [&](float z) -> float { return ENT ? fmaf(a, z, b) : b; };   // b = -g without the entropy term
   u32x4_t o;
   if constexpr (BF16) {
     float z[8], d[8];
     unpack8(v, z);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
+    for (int e = 0; e < 8; ++e) d[e] = scale(z[e]) * exp2_fast(fmaf(z[e], kLog2e, c));
     if (k == (y >> 3)) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
@@ -274,7 +305,7 @@ __device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, f
   } else {
     float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
 #pragma unroll
-    for (int e = 0; e < 4; ++e) d[e] = ng * exp2_fast(fmaf(d[e], kLog2e, c));
+    for (int e = 0; e < 4; ++e) d[e] = scale(d[e]) * exp2_fast(fmaf(d[e], kLog2e, c));
     if (k == (y >> 2)) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) d[e] += (e == (y & 3)) ? g : 0.f;
@@ -285,15 +316,18 @@ __device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, f
   return o;
 }
 
-template <bool BF16>
+template <bool BF16, bool ENT>
 __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
     const void* logits, int V, int64_t ld, int segs, const int32_t* __restrict__ targets,
-    const float* __restrict__ lse, const float* __restrict__ g_arr, void* dlogits) {
+    const float* __restrict__ lse, const float* __restrict__ g_arr, const float* __restrict__ ea,
+    const float* __restrict__ eb, void* dlogits) {
   constexpr int E = BF16 ? 8 : 4;
   constexpr size_t kEltBytes = BF16 ? 2 : 4;
   const int64_t t = blockIdx.x / segs;
   const int seg = blockIdx.x % segs;
   const float g = g_arr[t];
+  float a = 0.f;
+  if constexpr (ENT) a = ea[t];
   const size_t row_off = size_t(t) * size_t(ld) * kEltBytes;
   const char* zrow = reinterpret_cast<const char*>(logits) + row_off;
   char* drow = reinterpret_cast<char*>(dlogits) + row_off;
@@ -301,7 +335,7 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
   const int k0 = seg * kSegVecs + threadIdx.x;
   const int j = nvec * E + threadIdx.x;          // ragged tail, done by segment 0
   const bool tail = seg == 0 && j < V;
-  if (g == 0.f) {   // uniform over the workgroup: nothing to read
+  if (g == 0.f && a == 0.f) {   // uniform over the workgroup: nothing to read
 #pragma unroll
     for (int i = 0; i < kSegVPT; ++i)
       if (k0 + i * kSegNT < nvec) reinterpret_cast<u32x4_t*>(drow)[k0 + i * kSegNT] = u32x4_t{0u, 0u, 0u, 0u};
@@ -317,59 +351,78 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
     if (k0 + i * kSegNT < nvec) v[i] = reinterpret_cast<const u32x4_t*>(zrow)[k0 + i * kSegNT];
   const int y = targets[t];
   const float c = -lse[t] * kLog2e;
-  const float ng = -g;
+  float b = -g;
+  if constexpr (ENT) b = eb[t];
 #pragma unroll
   for (int i = 0; i < kSegVPT; ++i) {
     const int k = k0 + i * kSegNT;
-    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = dlogits_vec<BF16>(v[i], k, y, g, ng, c);
+    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = dlogits_vec<BF16, ENT>(v[i], k, y, g, a, b, c);
   }
   if (tail) {
     if constexpr (BF16) {
       const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
-      float d = ng * exp2_fast(fmaf(z, kLog2e, c));
+      float d = (ENT ? fmaf(a, z, b) : b) * exp2_fast(fmaf(z, kLog2e, c));
       if (j == y) d += g;
       reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(d);
     } else {
-      float d = ng * exp2_fast(fmaf(reinterpret_cast<const float*>(zrow)[j], kLog2e, c));
+      const float z = reinterpret_cast<const float*>(zrow)[j];
+      float d = (ENT ? fmaf(a, z, b) : b) * exp2_fast(fmaf(z, kLog2e, c));
       if (j == y) d += g;
       reinterpret_cast<float*>(drow)[j] = d;
     }
   }
 }
 
-template <bool BF16, bool VEC>
+template <bool BF16, bool VEC, bool ENT>
 static void dispatch_dlogits(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
-                             const float* lse, const float* g, void* dlogits, hipStream_t s) {
+                             const float* lse, const float* g, const float* ea, const float* eb, void* dlogits,
+                             hipStream_t s) {
   const int per_vec = VEC ? (BF16 ? 8 : 4) : 1;
   const int64_t work = (V + per_vec - 1) / per_vec;
   if constexpr (VEC) {
     const int64_t segs = (V / per_vec + kSegVecs - 1) / kSegVecs;
     if (work > 16 * 256 && T * segs < (int64_t(1) << 31)) {
-      hipLaunchKernelGGL((k_dlogits_seg<BF16>), dim3(unsigned(T * segs)), dim3(kSegNT), 0, s, logits, V, ld, int(segs),
-                         targets, lse, g, dlogits);
+      hipLaunchKernelGGL((k_dlogits_seg<BF16, ENT>), dim3(unsigned(T * segs)), dim3(kSegNT), 0, s, logits, V, ld,
+                         int(segs), targets, lse, g, ea, eb, dlogits);
       return;
     }
   }
   if (work <= 4 * 64)
-    hipLaunchKernelGGL((k_dlogits<64, BF16, VEC>), dim3((unsigned)T), dim3(64), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+    hipLaunchKernelGGL((k_dlogits<64, BF16, VEC, ENT>), dim3((unsigned)T), dim3(64), 0, s, logits, T, V, ld, targets,
+                       lse, g, ea, eb, dlogits);
   else if (work <= 16 * 256)
-    hipLaunchKernelGGL((k_dlogits<256, BF16, VEC>), dim3((unsigned)T), dim3(256), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+    hipLaunchKernelGGL((k_dlogits<256, BF16, VEC, ENT>), dim3((unsigned)T), dim3(256), 0, s, logits, T, V, ld, targets,
+                       lse, g, ea, eb, dlogits);
   else
-    hipLaunchKernelGGL((k_dlogits<512, BF16, VEC>), dim3((unsigned)T), dim3(512), 0, s, logits, T, V, ld, targets, lse, g, dlogits);
+    hipLaunchKernelGGL((k_dlogits<512, BF16, VEC, ENT>), dim3((unsigned)T), dim3(512), 0, s, logits, T, V, ld, targets,
+                       lse, g, ea, eb, dlogits);
+}
+
+template <bool ENT>
+static void dispatch_dlogits_dtype(int32_t dtype, bool vec, const void* logits, int64_t T, int V, int64_t ld,
+                                   const int32_t* targets, const float* lse, const float* g, const float* ea,
+                                   const float* eb, void* dlogits, hipStream_t s) {
+  if (dtype == AERO_BF16) {
+    if (vec) dispatch_dlogits<true, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<true, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+  } else {
+    if (vec) dispatch_dlogits<false, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<false, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+  }
 }
 
 // Shared with the fused LM-head path: token terms from given log-probs, then the reduction.
 aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
-                                     const float* old_logprob, const int32_t* token_rollout,
-                                     const float* adv, const float* weight, int R, float eps_lo,
-                                     float eps_hi, float grad_scale, float* g, float* term,
-                                     int32_t* flag, float* loss, float* clip_frac, int32_t* err_flag,
-                                     hipStream_t s) {
+                                     const float* lse, const float* entropy, const float* old_logprob,
+                                     const int32_t* token_rollout, const float* adv, const float* weight, int R,
+                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float* g,
+                                     float* term, int32_t* flag, float* ea, float* eb, float* loss,
+                                     float* clip_frac, int32_t* err_flag, hipStream_t s) {
   const unsigned blocks = unsigned((T + 255) / 256);
   if (T > 0)
     hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
-                       targets, nullptr, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                       grad_scale, g, term, flag, nullptr, err_flag);
+                       targets, lse, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                       grad_scale, ent_coef, entropy, g, term, flag, ea, eb, nullptr, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, term, flag, T, loss, clip_frac);
   return launch_status();
 }
@@ -378,11 +431,14 @@ aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, c
 
 extern "C" aero_status aero_grpo_loss_bwd(
     const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
-    const float* lse, const float* old_logprob, const int32_t* token_rollout, const float* adv,
-    const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale, float* loss,
-    float* clip_frac, float* logprob_out, float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag,
-    void* workspace, size_t workspace_bytes, void* stream) {
+    const float* lse, const float* entropy, const float* old_logprob, const int32_t* token_rollout,
+    const float* adv, const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale,
+    float entropy_coef, float* loss, float* clip_frac, float* logprob_out, float* entropy_out, float* lse_out,
+    void* dlogits, int32_t* err_flag, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace aero;
+  const bool ent = entropy_coef != 0.f;
+  if (!(entropy_coef == entropy_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
+  if (lse && ent && !entropy) return AERO_ERR_NULL;             // H_t must come with the given lse
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
   if (dtype != AERO_BF16 && dtype != AERO_F32) return AERO_ERR_DTYPE;
   if (!loss) return AERO_ERR_NULL;
@@ -401,7 +457,7 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (!lse) {
     // statistics are computed here; with entropy_out / lse_out they cover every valid row
     const int stats_all = (entropy_out || lse_out) ? 1 : 0;
-    if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
+    if (!ent && single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
                                                 eps_lo, eps_hi, grad_scale, stats_all, ws.g, ws.loss_term, ws.flag,
                                                 logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter, s);
@@ -410,13 +466,15 @@ extern "C" aero_status aero_grpo_loss_bwd(
       return launch_status();
     }
     hipLaunchKernelGGL(k_signal_mask, dim3(blocks), dim3(256), 0, s, T, V, targets, token_rollout, adv, weight,
-                       R, stats_all, ws.signal);
+                       R, stats_all, ent ? 1 : 0, ws.signal);
     float* lse_dst = lse_out ? lse_out : ws.lse;
+    float* ent_dst = entropy_out ? entropy_out : (ent ? ws.ent : nullptr);
     aero_status st = logprob_fwd_launch(logits, dtype, T, V, ld, targets, ws.signal,
-                                        stats_all && logprob_out ? logprob_out : ws.lp_tmp, entropy_out, lse_dst,
+                                        stats_all && logprob_out ? logprob_out : ws.lp_tmp, ent_dst, lse_dst,
                                         nullptr, s);
     if (st != AERO_OK) return st;
     lse = lse_dst;
+    entropy = ent_dst;
     if (stats_all) lp_dst = nullptr;   // already written for every valid row by the forward pass
   } else if (entropy_out || lse_out) {
     return AERO_ERR_NULL;   // these outputs exist only when the statistics are computed here
@@ -424,23 +482,20 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (dtype == AERO_BF16)
     hipLaunchKernelGGL((k_token_terms<true, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       ws.g, ws.loss_term, ws.flag, lp_dst, err_flag);
+                       entropy_coef, entropy, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr, ent ? ws.eb : nullptr,
+                       lp_dst, err_flag);
   else
     hipLaunchKernelGGL((k_token_terms<false, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       ws.g, ws.loss_term, ws.flag, lp_dst, err_flag);
+                       entropy_coef, entropy, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr, ent ? ws.eb : nullptr,
+                       lp_dst, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
   if (dlogits) {
     const size_t elt = dtype == AERO_BF16 ? 2 : 4;
     const bool vec = reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0 &&
                      (size_t(ld) * elt) % 16 == 0;
-    if (dtype == AERO_BF16) {
-      if (vec) dispatch_dlogits<true, true>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
-      else dispatch_dlogits<true, false>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
-    } else {
-      if (vec) dispatch_dlogits<false, true>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
-      else dispatch_dlogits<false, false>(logits, T, V, ld, targets, lse, ws.g, dlogits, s);
-    }
+    if (ent) dispatch_dlogits_dtype<true>(dtype, vec, logits, T, V, ld, targets, lse, ws.g, ws.ea, ws.eb, dlogits, s);
+    else dispatch_dlogits_dtype<false>(dtype, vec, logits, T, V, ld, targets, lse, ws.g, nullptr, nullptr, dlogits, s);
   }
   return launch_status();
 }

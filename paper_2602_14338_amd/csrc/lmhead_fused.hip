@@ -26,11 +26,11 @@
 namespace aero {
 
 aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
-                                     const float* old_logprob, const int32_t* token_rollout,
-                                     const float* adv, const float* weight, int R, float eps_lo,
-                                     float eps_hi, float grad_scale, float* g, float* term,
-                                     int32_t* flag, float* loss, float* clip_frac, int32_t* err_flag,
-                                     hipStream_t s);
+                                     const float* lse, const float* entropy, const float* old_logprob,
+                                     const int32_t* token_rollout, const float* adv, const float* weight, int R,
+                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float* g,
+                                     float* term, int32_t* flag, float* ea, float* eb, float* loss,
+                                     float* clip_frac, int32_t* err_flag, hipStream_t s);
 
 constexpr size_t kWsAlign = 256;
 inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -41,7 +41,8 @@ inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct FusedPlan {
   int64_t T, T_pad;
   int V, V_ld, H, H_pad, tiles_v, VC;   // VC: vocabulary chunk of the backward pass
-  size_t off_part, off_fidx, off_nf, off_g, off_term, off_flag, off_idx, off_pos, off_nact, off_gc, off_lsec, off_yc,
+  size_t off_part, off_fidx, off_nf, off_g, off_term, off_flag, off_ea, off_eb, off_ent, off_idx, off_pos, off_nact,
+      off_gc, off_lsec, off_yc, off_ac, off_bc,
       off_hc, off_hTc, off_WT, off_dz, off_dzT, off_dhacc, total;
 };
 
@@ -81,12 +82,17 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.off_g = take(size_t(p.T_pad) * 4);
   p.off_term = take(size_t(p.T_pad) * 4);
   p.off_flag = take(size_t(p.T_pad) * 4);
+  p.off_ea = take(size_t(p.T_pad) * 4);
+  p.off_eb = take(size_t(p.T_pad) * 4);
+  p.off_ent = take(size_t(p.T_pad) * 4);
   p.off_idx = take(size_t(p.T_pad) * 4);
   p.off_pos = take(size_t(p.T_pad) * 4);
   p.off_nact = take(16);
   p.off_gc = take(size_t(p.T_pad) * 4);
   p.off_lsec = take(size_t(p.T_pad) * 4);
   p.off_yc = take(size_t(p.T_pad) * 4);
+  p.off_ac = take(size_t(p.T_pad) * 4);
+  p.off_bc = take(size_t(p.T_pad) * 4);
   p.off_hc = take(size_t(p.T_pad) * H * 2);
   p.off_hTc = take(size_t(p.H_pad) * p.T_pad * 2);
   p.off_WT = take(size_t(p.H_pad) * p.V_ld * 2);
@@ -279,18 +285,23 @@ __global__ __launch_bounds__(256) void k_fused_combine(
 // ------------------------------------------------------------------------------------------
 // backward: compaction, transposes
 // ------------------------------------------------------------------------------------------
-// Single workgroup, order-preserving: idx[j] = j-th token with g != 0, pos[t] = j or -1,
-// nact[0] = count, nact[1] = count rounded up to a tile.  Compacted per-token scalars follow.
+// Single workgroup, order-preserving: idx[j] = j-th token with a gradient row (g != 0, or with
+// the entropy bonus a != 0), pos[t] = j or -1, nact[0] = count, nact[1] = count rounded up to a
+// tile.  Compacted per-token scalars follow: the row is dz_j = pi_j (ac z_j + bc) + gc 1[j = y],
+// with (ac, bc) = (0, -g) when there is no entropy bonus (ea == null).
 __global__ __launch_bounds__(1024) void k_compact_tokens(
-    const float* __restrict__ g, const float* __restrict__ lse, const int32_t* __restrict__ targets, int64_t T,
+    const float* __restrict__ g, const float* __restrict__ ea, const float* __restrict__ eb,
+    const float* __restrict__ lse, const int32_t* __restrict__ targets, int64_t T,
     int64_t T_pad, int32_t* __restrict__ idx, int32_t* __restrict__ pos, int32_t* __restrict__ nact,
-    float* __restrict__ gc, float* __restrict__ lsec, int32_t* __restrict__ yc) {
+    float* __restrict__ gc, float* __restrict__ lsec, int32_t* __restrict__ yc, float* __restrict__ ac,
+    float* __restrict__ bc) {
   __shared__ int part[1024];
   const int tid = threadIdx.x;
   const int64_t per = (T + 1023) / 1024;
   const int64_t lo = min(T, tid * per), hi = min(T, lo + per);
+  auto active = [&](int64_t t) -> bool { return g[t] != 0.f || (ea && ea[t] != 0.f); };
   int cnt = 0;
-  for (int64_t t = lo; t < hi; ++t) cnt += g[t] != 0.f;
+  for (int64_t t = lo; t < hi; ++t) cnt += active(t);
   part[tid] = cnt;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {
@@ -302,12 +313,14 @@ __global__ __launch_bounds__(1024) void k_compact_tokens(
   int run = tid ? part[tid - 1] : 0;
   const int total = part[1023];
   for (int64_t t = lo; t < hi; ++t) {
-    if (g[t] != 0.f) {
+    if (active(t)) {
       idx[run] = int(t);
       pos[t] = run;
       gc[run] = g[t];
       lsec[run] = lse[t];
       yc[run] = targets[t];
+      ac[run] = ea ? ea[t] : 0.f;
+      bc[run] = ea ? eb[t] : -g[t];
       ++run;
     } else {
       pos[t] = -1;
@@ -318,6 +331,8 @@ __global__ __launch_bounds__(1024) void k_compact_tokens(
     gc[j] = 0.f;
     lsec[j] = 0.f;
     yc[j] = -1;
+    ac[j] = 0.f;
+    bc[j] = 0.f;
   }
   if (tid == 0) {
     nact[0] = total;
@@ -411,11 +426,15 @@ __global__ __launch_bounds__(256) void k_gather_transpose_vec(
 // the two K-slab layouts the next two contractions read: dz as [v / 64][token][64] (K = vocab)
 // and dzT as [token / 64][v][64] (K = tokens); entries outside the vocabulary or the active
 // tokens are zero.
+// ENT: rows also carry the entropy-bonus term, dz = pi (ac z + bc) + gc onehot; otherwise ac = 0
+// and the scale is the per-token constant bc = -g.
+template <bool ENT>
 __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hc, int V, int H, int v0, int vc,
     int tiles_v, int tiles_t, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
     const float* __restrict__ gc, const float* __restrict__ lsec, const int32_t* __restrict__ yc,
-    uint16_t* __restrict__ dz, uint16_t* __restrict__ dzT) {
+    const float* __restrict__ ac, const float* __restrict__ bc, uint16_t* __restrict__ dz,
+    uint16_t* __restrict__ dzT) {
   extern __shared__ __align__(16) uint16_t smem[];
   int tv, tt;
   tile_of_block(tiles_v, tiles_t, tv, tt);
@@ -431,7 +450,8 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 #pragma unroll
   for (int nb = 0; nb < kNB; ++nb) {
     const int64_t t = n0 + acc_col(wn, nb, lane);
-    const float g = gc[t], ng = -g;
+    const float g = gc[t], ng = bc[t];   // bc = -g without the entropy bonus
+    const float a = ENT ? ac[t] : 0.f;
     const float c = -lsec[t] * kLog2e;
     const int yrel = yc[t] - v0;   // row of the sampled token inside this chunk, if any
     // Almost every wave holds neither a sampled token's row nor rows past the vocabulary: that
@@ -444,7 +464,10 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
         for (int i4 = 0; i4 < 4; ++i4) {
           float d[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) d[j] = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
+          for (int j = 0; j < 4; ++j) {
+            const float z = acc[mb][nb][i4 * 4 + j];
+            d[j] = (ENT ? fmaf(a, z, ng) : ng) * exp2_fast(fmaf(z, kLog2e, c));
+          }
           pk[nb][mb][i4][0] = pack_bf16x2(d[0], d[1]);
           pk[nb][mb][i4][1] = pack_bf16x2(d[2], d[3]);
         }
@@ -457,7 +480,8 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const int row = m0 + acc_row(wm, mb, i4 * 4 + j, lane);
-            float v = ng * exp2_fast(fmaf(acc[mb][nb][i4 * 4 + j], kLog2e, c));
+            const float z = acc[mb][nb][i4 * 4 + j];
+            float v = (ENT ? fmaf(a, z, ng) : ng) * exp2_fast(fmaf(z, kLog2e, c));
             if (row == yrel) v += g;
             d[j] = row < vc ? v : 0.f;
           }
@@ -653,9 +677,10 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     const void* hidden, const void* weight, int64_t T, int32_t H, int32_t V, const int32_t* targets,
     float* logprob, float* entropy, float* lse, const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight_rollout, int32_t R, float eps_lo, float eps_hi, float grad_scale,
-    float* loss, float* clip_frac, void* dhidden, void* dweight, int32_t dweight_dtype, int32_t* err_flag,
-    void* workspace, size_t workspace_bytes, void* stream) {
+    float entropy_coef, float* loss, float* clip_frac, void* dhidden, void* dweight, int32_t dweight_dtype,
+    int32_t* err_flag, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace aero;
+  if (!(entropy_coef == entropy_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
   if (T < 0 || T > 0x7fffff00LL || V < 1 || V > (1 << 24) || H < 8 || H % 8 != 0 || H > (1 << 20) || R < 0)
     return AERO_ERR_SHAPE;
   const bool bwd = old_logprob != nullptr;
@@ -687,7 +712,8 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   static aero_status attr_rc = AERO_OK;
   std::call_once(attr_once, [] {
     if (set_lds(reinterpret_cast<const void*>(k_fused_stats)) != AERO_OK ||
-        set_lds(reinterpret_cast<const void*>(k_fused_dz), kDzLdsBytes) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_fused_dz<false>), kDzLdsBytes) != AERO_OK ||
+        set_lds(reinterpret_cast<const void*>(k_fused_dz<true>), kDzLdsBytes) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dh)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<true>)) != AERO_OK ||
         set_lds(reinterpret_cast<const void*>(k_gemm_dw<false>)) != AERO_OK)
@@ -699,14 +725,16 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   int32_t* fidx = reinterpret_cast<int32_t*>(ws + p.off_fidx);
   int32_t* nf = reinterpret_cast<int32_t*>(ws + p.off_nf);
   uint16_t* hf = reinterpret_cast<uint16_t*>(ws + p.off_hc);   // forward use of the gathered-rows buffer
+  const bool ent = bwd && entropy_coef != 0.f;
+  float* ent_arr = entropy ? entropy : (ent ? reinterpret_cast<float*>(ws + p.off_ent) : nullptr);
   if (T > 0) {
-    hipLaunchKernelGGL(k_compact_valid, dim3(1), dim3(1024), 0, s, targets, T, p.T_pad, V, fidx, nf, logprob, entropy,
+    hipLaunchKernelGGL(k_compact_valid, dim3(1), dim3(1024), 0, s, targets, T, p.T_pad, V, fidx, nf, logprob, ent_arr,
                        lse, err_flag);
     hipLaunchKernelGGL(k_gather_rows, dim3(unsigned(p.T_pad / 4)), dim3(256), 0, s, Hp, H, fidx, p.T_pad, hf);
     hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(p.tiles_v * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hf,
                        V, H, p.tiles_v, tiles_t, p.T_pad, nf, part_m, part_s, part_sz);
     hipLaunchKernelGGL(k_fused_combine, dim3(unsigned(p.T_pad / kCombineTokens)), dim3(256), 0, s, Wp, hf, H,
-                       p.tiles_v, p.T_pad, fidx, nf, part_m, part_s, part_sz, targets, logprob, entropy, lse);
+                       p.tiles_v, p.T_pad, fidx, nf, part_m, part_s, part_sz, targets, logprob, ent_arr, lse);
   }
   if (!bwd) return launch_status();
 
@@ -714,8 +742,11 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   float* g = reinterpret_cast<float*>(ws + p.off_g);
   float* term = reinterpret_cast<float*>(ws + p.off_term);
   int32_t* flag = reinterpret_cast<int32_t*>(ws + p.off_flag);
-  aero_status st = token_terms_from_logprob(T, V, targets, logprob, old_logprob, token_rollout, adv, weight_rollout,
-                                            R, eps_lo, eps_hi, grad_scale, g, term, flag, loss, clip_frac, err_flag, s);
+  float* ea = ent ? reinterpret_cast<float*>(ws + p.off_ea) : nullptr;
+  float* eb = ent ? reinterpret_cast<float*>(ws + p.off_eb) : nullptr;
+  aero_status st = token_terms_from_logprob(T, V, targets, logprob, lse, ent_arr, old_logprob, token_rollout, adv,
+                                            weight_rollout, R, eps_lo, eps_hi, grad_scale, entropy_coef, g, term, flag,
+                                            ea, eb, loss, clip_frac, err_flag, s);
   if (st != AERO_OK) return st;
 
   // ---- compaction and operand copies ----
@@ -732,8 +763,10 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   uint16_t* dzT = reinterpret_cast<uint16_t*>(ws + p.off_dzT);
   float* dh_acc = reinterpret_cast<float*>(ws + p.off_dhacc);
 
-  hipLaunchKernelGGL(k_compact_tokens, dim3(1), dim3(1024), 0, s, g, lse, targets, T, p.T_pad, idx, pos, nact, gc,
-                     lsec, yc);
+  float* ac = reinterpret_cast<float*>(ws + p.off_ac);
+  float* bc = reinterpret_cast<float*>(ws + p.off_bc);
+  hipLaunchKernelGGL(k_compact_tokens, dim3(1), dim3(1024), 0, s, g, ea, eb, lse, targets, T, p.T_pad, idx, pos, nact,
+                     gc, lsec, yc, ac, bc);
   // hidden rows gathered to hc [T_pad, H] and transposed to hTc, K-slabs over the compacted tokens
   const bool vec_tr = (H % 8 == 0) && (reinterpret_cast<uintptr_t>(Hp) % 16 == 0) && (reinterpret_cast<uintptr_t>(Wp) % 16 == 0);
   const auto transpose = vec_tr ? k_gather_transpose_vec : k_gather_transpose;
@@ -750,8 +783,12 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     const int vc = (V - v0 < p.VC) ? V - v0 : p.VC;
     const int tiles_vc = (vc + kTile - 1) / kTile;
     const int vcK = (vc + kDK - 1) / kDK * kDK;   // dz columns [vc, vcK) are zero, WT is zero past V
-    hipLaunchKernelGGL(k_fused_dz, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V, H,
-                       v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, dz, dzT);
+    if (ent)
+      hipLaunchKernelGGL(k_fused_dz<true>, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V,
+                         H, v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
+    else
+      hipLaunchKernelGGL(k_fused_dz<false>, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V,
+                         H, v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
     hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, WT,
                        p.H_pad, v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
     if (dweight_dtype == AERO_BF16)

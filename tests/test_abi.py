@@ -43,7 +43,7 @@ def test_status_strings_and_workspace_sizes_on_host():
     assert aero.aero_workspace_bytes(binding.OP_GROUP_ADVANTAGE, T=10) == 0
     assert aero.aero_workspace_bytes(binding.OP_LOGPROB_FWD, T=10, V=100) == 0
     a = aero.aero_workspace_bytes(binding.OP_GRPO_LOSS_BWD, T=16384, V=151936)
-    assert a % 256 == 0 and 16384 * 4 * 5 <= a <= 16384 * 4 * 8
+    assert a % 256 == 0 and 16384 * 4 * 5 <= a <= 16384 * 4 * 10
     f4 = aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=16384, V=151936, H=1536)
     f5 = aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=32768, V=152064, H=3584)
     assert 0 < f4 < 4 << 30 and f4 < f5 < 6 << 30

@@ -45,7 +45,8 @@ def run_fused(gh, wl, h_bits, w_bits, targets, bwd=None, dweight_dtype=torch.flo
         aero.aero_lmhead_logprob_fused(
             hd, wd, T, H, V, gh.dev(targets), lp, ent, lse, gh.dev(bwd["old"].astype(np.float32)),
             gh.dev(wl.token_rollout), gh.dev(bwd["adv"].astype(np.float32)), gh.dev(bwd["weight"].astype(np.float32)),
-            wl.R, 0.2, 0.2, bwd.get("grad_scale", 1.0), loss, clip, dh, dw, ws, err)
+            wl.R, 0.2, 0.2, bwd.get("grad_scale", 1.0), loss, clip, dh, dw, ws, err,
+            entropy_coef=bwd.get("entropy_coef", 0.0))
         out.update(loss=loss, clip_frac=clip, dhidden=dh, dweight=dw)
     torch.cuda.synchronize()
     out["err"] = int(err.item())
@@ -84,14 +85,15 @@ def test_fused_forward(gh, T, H, V):
         assert not got[tg < 0].any()
 
 
-def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, grad_scale=1.0):
+def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, grad_scale=1.0, entropy_coef=0.0):
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     fwd = orc.lmhead_fused(h, W, wl.targets)
     old = ai.draw_old_logprob(fwd["logprob"], wl.seed, sigma=sigma_old)
     a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
     ref = orc.lmhead_fused(h, W, wl.targets, old, wl.token_rollout, a32, w32, np.float32(0.2), np.float32(0.2),
-                           grad_scale)
-    out = run_fused(gh, wl, h, W, wl.targets, bwd=dict(old=old, adv=a32, weight=w32, grad_scale=grad_scale),
+                           grad_scale, entropy_coef=entropy_coef)
+    out = run_fused(gh, wl, h, W, wl.targets,
+                    bwd=dict(old=old, adv=a32, weight=w32, grad_scale=grad_scale, entropy_coef=entropy_coef),
                     dweight_dtype=dweight_dtype)
     assert out["err"] == 0
     assert abs(out["loss"].item() - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"])
@@ -101,7 +103,7 @@ def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, 
     assert np.isfinite(dh).all() and np.isfinite(dw).all()
     assert rowwise_close(dh, ref["dhidden"])
     assert rowwise_close(dw, ref["dweight"])
-    dead = ref["g"] == 0
+    dead = (ref["g"] == 0) & (ref["e"] == 0)
     assert not out["dhidden"].view(torch.int16)[torch.from_numpy(dead).to(gh.DEV)].any()   # +0 rows
     return ref, out
 
@@ -119,6 +121,20 @@ def test_fused_backward_several_chunks_and_recipe_scale(gh):
     """Vocabulary wider than one backward chunk at this T (2 x 24576 > chunk), paper-scale weights."""
     wl, h, W = make(2816, 128, 40000, Q=8, len_hi=500)
     check_bwd(gh, wl, h, W, dict(), sigma_old=0.05)
+
+
+def test_fused_entropy_bonus(gh):
+    """Entropy bonus through the fused path: more rows carry gradient (advantage-0 rollouts with a
+    weight), loss and both gradients follow the checker."""
+    wl, h, W = make(520, 128, 1000, sigma_w=0.3)
+    ref0, _ = check_bwd(gh, wl, h, W, dict())
+    for coef in (1e-3, 0.05):
+        ref, _ = check_bwd(gh, wl, h, W, dict(), entropy_coef=coef)
+        assert (ref["e"] != 0).sum() > (ref0["g"] != 0).sum() and ref["loss"] < ref0["loss"]
+    check_bwd(gh, wl, h, W, dict(reject_enable=1, posterior_mode=1), entropy_coef=0.01, dweight_dtype=torch.bfloat16,
+              grad_scale=8.0)
+    wl, h, W = make(2816, 128, 40000, Q=8, len_hi=500)     # several vocabulary chunks
+    check_bwd(gh, wl, h, W, dict(), sigma_old=0.05, entropy_coef=1e-3)
 
 
 def test_fused_all_groups_zero_variance(gh):

@@ -195,7 +195,7 @@ def elt_rounding(dtype, ref_abs):
 
 
 def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
-                   expect_clip=False, stats=False):
+                   expect_clip=False, stats=False, entropy_coef=0.0):
     host = wl.logits_rows(0, wl.T)
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     active = (wl.token_rollout >= 0).astype(np.uint8)
@@ -203,11 +203,13 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=sigma_old)
     eps = np.float32(wl.eps)
     ref = orc.grpo_loss_bwd(host, wl.dtype, wl.V, wl.targets, old, wl.token_rollout, ga["adv"].astype(np.float32),
-                            ga["weight"].astype(np.float32), eps, eps, grad_scale)
+                            ga["weight"].astype(np.float32), eps, eps, grad_scale, entropy_coef=entropy_coef)
     d = gh.logits_to_dev(host, wl.dtype)
     lse_d = gh.dev(lse_ref.astype(np.float32)) if use_oracle_lse else None
     out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, wl.token_rollout,
-                          ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace, stats=stats)
+                          ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace, stats=stats,
+                          entropy_coef=entropy_coef,
+                          entropy=ent_ref if (use_oracle_lse and entropy_coef != 0.0) else None)
     assert out["err"] == 0
     loss = out["loss"].item()
     assert abs(loss - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"]), (loss, ref["loss"])
@@ -226,9 +228,11 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     want = ref["dlogits"]
     assert np.isfinite(dz).all()
     assert np.abs(dz - want).max() <= DZ_ATOL
-    bound = 1e-2 * np.abs(ref["g"])[:, None] + elt_rounding(wl.dtype, np.abs(want))
+    # scale of a row: |g_t| for the surrogate, |e_t| (|p ln p| + p H_t) <= |e_t| (1 + H_t) for the entropy term
+    scale = np.abs(ref["g"]) + np.abs(ref["e"]) * (1.0 + ent_ref)
+    bound = 1e-2 * scale[:, None] + elt_rounding(wl.dtype, np.abs(want))
     assert (np.abs(dz - want) <= bound).all()
-    dead = ref["g"] == 0
+    dead = (ref["g"] == 0) & (ref["e"] == 0)
     raw = out["dlogits"][:, :wl.V]
     bits = raw.view(torch.int16) if wl.dtype == "bf16" else raw.view(torch.int32)
     assert not bits[torch.from_numpy(dead).to(gh.DEV)].any()       # exactly +0, sign bit included
@@ -244,6 +248,38 @@ def test_loss_bwd_cfg1_full(gh):
     check_loss_bwd(gh, wl, dict(), use_oracle_lse=False)
     check_loss_bwd(gh, wl, dict(), sigma_old=0.3, expect_clip=True)
     check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, inplace=True, grad_scale=64.0)
+
+
+def test_entropy_bonus_cfg1(gh):
+    """Entropy bonus (Table 8 coefficient and a large one): rows of the all-equal groups now
+    carry the entropy-only gradient, rows of dropped rollouts stay exactly +0."""
+    wl = ai.make_config("cfg1")
+    ref0, _ = check_loss_bwd(gh, wl, dict())
+    for coef in (1e-3, 0.05):
+        ref, _ = check_loss_bwd(gh, wl, dict(), entropy_coef=coef)
+        assert (ref["e"] != 0).sum() > (ref0["g"] != 0).sum() and ref["loss"] < ref0["loss"]
+        assert ((ref["g"] == 0) & (ref["e"] != 0)).any()
+        check_loss_bwd(gh, wl, dict(), use_oracle_lse=False, sigma_old=0.3, expect_clip=True, entropy_coef=coef,
+                       grad_scale=16.0)
+    # curation drops rollouts (weight 0): their rows have neither term
+    ref, _ = check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), entropy_coef=0.01, inplace=True)
+    assert ((ref["e"] == 0) & (wl.token_rollout >= 0)).any()
+
+
+@pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10)])
+def test_entropy_bonus_cfg2_reduced(gh, V, ld, slots):
+    wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
+    check_loss_bwd(gh, wl, dict(), entropy_coef=1e-3)
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, expect_clip=True, entropy_coef=0.02, stats=True)
+
+
+def test_entropy_bonus_needs_the_entropy_array(gh):
+    wl = ai.make_config("cfg1")
+    d = gh.logits_to_dev(wl.logits_rows(0, wl.T), wl.dtype)
+    lse = torch.zeros(wl.T, device=gh.DEV)
+    with pytest.raises(Exception):
+        gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse, np.zeros(wl.T), wl.token_rollout,
+                        np.zeros(wl.R), np.zeros(wl.R), entropy_coef=1e-3)
 
 
 # V >= 8192 with aligned rows takes the single-pass kernel when lse is not given: 151936 and
