@@ -17,12 +17,16 @@ in float64, step by step as the paper states it:
                     (1/N and 1/|o_i| weights).
   logprob_fwd       App. C softmax policy; log-prob of the sampled token; entropy.
   grpo_loss_bwd     Eq. 2 clipped surrogate (beta = 0) and its gradient w.r.t. the
-                    logits, App. A.1 (gradient of the ratio, clipped tokens give zero).
+                    logits, App. A.1 (gradient of the ratio, clipped tokens give zero);
+                    optional entropy bonus (Table 8 coefficient).
   lmhead_fused      the same, with logits defined as hidden @ weight^T.
 
 Readings of points the paper leaves open are listed next to the code that takes
-them.  One of them has no external pin ("parity unpinned"): in posterior mode the
-standard deviation that divides (r - u~) is taken as sqrt(u~ (1 - u~)).
+them.  Two of them have no external pin ("parity unpinned"): in posterior mode the
+standard deviation that divides (r - u~) is taken as sqrt(u~ (1 - u~)); and the entropy
+bonus, for which the paper gives a coefficient only, is aggregated with the weights of
+Eq. 2 over every token of a weighted rollout (the entropy and its gradient themselves are
+pinned).
 """
 from __future__ import annotations
 
