@@ -19,6 +19,7 @@ from .workloads import (
     LogitsWorkload,
     FusedWorkload,
     make_config,
+    make_step_groups,
     draw_old_logprob,
     normal_rows,
 )
@@ -28,6 +29,7 @@ __all__ = [
     "LogitsWorkload",
     "FusedWorkload",
     "make_config",
+    "make_step_groups",
     "draw_old_logprob",
     "normal_rows",
     "f32_to_bf16_bits",

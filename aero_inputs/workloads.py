@@ -307,3 +307,24 @@ def make_config(name: str, seed: Optional[int] = None, **ov):
     if ov:
         raise TypeError(f"unused overrides for {name}: {sorted(ov)}")
     return wl
+
+
+# --------------------------------------------------------------------------- one training step
+
+@dataclass
+class StepGroups(_Groups):
+    """The rollouts of one training step before curation: Q queries x N rollouts each."""
+    name: str = "step"
+    seed: int = 0
+
+
+def make_step_groups(seed: int = 5, Q: int = 256, N: int = 16, len_lo: int = 128, len_hi: int = 2048,
+                     zero_var_frac: float = 0.35, adv_params: Optional[dict] = None) -> StepGroups:
+    """Q groups of N rollouts: ``zero_var_frac`` of the groups have all-equal binary rewards, the
+    others a count of correct rollouts U{1..N-1}; response lengths U{len_lo..len_hi}."""
+    sizes, lengths, rewards, _ = _ragged_groups(seed, Q, N, N, len_lo, len_hi, zero_var_frac=zero_var_frac)
+    go = _offsets(sizes)
+    params = dict(ADV_PARAM_DEFAULTS)
+    params.update(adv_params or {})
+    return StepGroups(Q=Q, R=int(go[-1]), group_offsets=go, rewards=rewards, lengths=lengths,
+                      keep_priority=_priority(seed, int(go[-1])), adv_params=params, name="step", seed=seed)

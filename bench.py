@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5", "step"])
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
@@ -123,6 +123,8 @@ def main():
     name = args.workload
     if name in ("cfg4", "cfg5"):
         return bench_fused(args, torch, ai, aero, binding)
+    if name == "step":
+        return bench_step(args, torch, ai, aero, binding)
     wl = ai.make_config("cfg2" if name == "cfg2-dense" else name)
     if name == "cfg2-dense":   # same tensor shape, every slot a valid token
         wl.lengths[:] = wl.T // wl.R
@@ -299,6 +301,75 @@ def main():
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+
+
+def bench_step(args, torch, ai, aero, binding):
+    """One policy-update step (256 queries x 16 rollouts, 35 % of the groups with all-equal
+    rewards) through the logits path, micro-batch by micro-batch, with plain grouping and with
+    AERO's curation.  Reports how many rollouts / tokens each mode trains on and the time of the
+    curation call plus all loss / gradient calls.  One resident [mb_tokens, V] bf16 logits
+    buffer serves every micro-batch (its content does not change the work done per row); the
+    model forward / backward and rollout generation are outside this path."""
+    from paper_2602_14338_amd import step
+    dev = "cuda:0"
+    V, mb_tokens = 151936, 16384
+    groups = ai.make_step_groups()
+    wl = ai.make_config("cfg2")
+
+    def d(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+
+    logits = torch.empty((mb_tokens, V), dtype=torch.bfloat16, device=dev)
+    for r0 in range(0, mb_tokens, 2048):
+        h = wl.logits_rows(r0, r0 + 2048, threads=args.gen_threads)
+        logits[r0:r0 + 2048].copy_(torch.from_numpy(h.view(np.int16)).view(torch.bfloat16))
+    dlogits = torch.empty_like(logits)
+    targets = d(wl.targets)
+    lp, lse = torch.empty(mb_tokens, device=dev), torch.empty(mb_tokens, device=dev)
+    aero.aero_logprob_fwd(logits, mb_tokens, V, V, targets, None, lp, None, lse)
+    g = torch.Generator(device=dev)
+    g.manual_seed(groups.seed)
+    old = (lp + 0.05 * torch.randn(mb_tokens, device=dev, generator=g)).contiguous()
+    rewards, lengths, offsets = d(groups.rewards), d(groups.lengths), d(groups.group_offsets)
+    keys = d(groups.keep_priority.view(np.int32))
+    out = {}
+    for mode, params in (("grpo", dict()), ("aero", dict(reject_enable=1, posterior_mode=1))):
+        p = aero.AdvParams(**params)
+        cur = step.curate(rewards, lengths, offsets, keys, p)
+        torch.cuda.synchronize()
+        keep = cur.keep_mask.cpu().numpy()
+        rollouts = np.nonzero(keep)[0]
+        plan = step.plan_microbatches(groups.lengths, rollouts, mb_tokens)   # data-loader work, untimed
+        plan_d = d(plan)
+        signal = (cur.adv.cpu().numpy()[rollouts] != 0) & (cur.weight.cpu().numpy()[rollouts] != 0)
+
+        def run():
+            c = step.curate(rewards, lengths, offsets, keys, p)
+            return step.loss_bwd_microbatches(plan_d, lambda k: logits, lambda k: targets, lambda k: old,
+                                              lambda k: dlogits, c.adv, c.weight, V, V, 0.2, 0.2)
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        losses = run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        out[mode] = {"rollouts_trained": int(rollouts.size), "rollouts_per_query": rollouts.size / groups.Q,
+                     "tokens_trained": int(groups.lengths[rollouts].sum()),
+                     "tokens_with_signal": int(groups.lengths[rollouts][signal].sum()),
+                     "micro_batches": int(plan.shape[0]), "ms": ms, "loss": float(losses.double().sum().item())}
+    gen_tokens = int(groups.lengths.sum())
+    res = {
+        "metric": "ms per policy-update step on the logits path (256 queries x 16 rollouts, V=151936), AERO-curated",
+        "value": out["aero"]["ms"], "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
+        "ms_per_step": out["aero"]["ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "step", "queries": groups.Q, "rollouts": groups.R, "generated_tokens": gen_tokens,
+                   "micro_batch_rows": mb_tokens, "V": V},
+        "grpo": out["grpo"], "aero": out["aero"],
+        "token_ratio_aero_over_grpo": out["aero"]["tokens_trained"] / out["grpo"]["tokens_trained"],
+        "time_ratio_aero_over_grpo": out["aero"]["ms"] / out["grpo"]["ms"],
+    }
+    print(json.dumps(res))
 
 
 def bench_fused(args, torch, ai, aero, binding):
