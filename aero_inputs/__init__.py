@@ -20,6 +20,7 @@ from .workloads import (
     FusedWorkload,
     make_config,
     make_step_groups,
+    RolloutSimulator,
     draw_old_logprob,
     normal_rows,
 )
@@ -30,6 +31,7 @@ __all__ = [
     "FusedWorkload",
     "make_config",
     "make_step_groups",
+    "RolloutSimulator",
     "draw_old_logprob",
     "normal_rows",
     "f32_to_bf16_bits",

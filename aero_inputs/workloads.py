@@ -24,7 +24,7 @@ from .bf16 import f32_to_bf16_bits
 ROWS_PER_BLOCK = 64
 
 # stream ids (second key of every generator)
-_S_STRUCT, _S_REWARD, _S_TARGET, _S_LOGITS, _S_HIDDEN, _S_WEIGHT, _S_OLDLP, _S_PRIO = range(8)
+_S_STRUCT, _S_REWARD, _S_TARGET, _S_LOGITS, _S_HIDDEN, _S_WEIGHT, _S_OLDLP, _S_PRIO, _S_SIM = range(9)
 
 # Hyper-parameters of the curation step as the paper sets them: 1:k ratio with k=1,
 # rescue threshold S=0, tau=1/2, 4 rollouts kept for all-equal groups, Beta(1,1) prior.
@@ -328,3 +328,30 @@ def make_step_groups(seed: int = 5, Q: int = 256, N: int = 16, len_lo: int = 128
     params.update(adv_params or {})
     return StepGroups(Q=Q, R=int(go[-1]), group_offsets=go, rewards=rewards, lengths=lengths,
                       keep_priority=_priority(seed, int(go[-1])), adv_params=params, name="step", seed=seed)
+
+
+# --------------------------------------------------------------------------- rollout simulator
+
+class RolloutSimulator:
+    """Stands in for generation + verification: query q answers correctly with a latent
+    probability p_q ~ Beta(beta, beta).  The j-th rollout ever drawn for query q has a fixed
+    outcome and length (keyed by (seed, q), position j), so two controllers that ask for the
+    same positions see the same rollouts, whatever order they ask in."""
+
+    def __init__(self, seed: int, P: int, max_per_query: int = 32, beta: float = 0.5,
+                 len_lo: int = 128, len_hi: int = 2048, p_q: Optional[np.ndarray] = None):
+        self.seed, self.P, self.max_per_query = int(seed), int(P), int(max_per_query)
+        self.p_q = (_rng(seed, _S_SIM).beta(beta, beta, size=P) if p_q is None
+                    else np.asarray(p_q, np.float64).copy())
+        assert self.p_q.shape == (P,)
+        self.len_lo, self.len_hi = int(len_lo), int(len_hi)
+
+    def draw(self, q: int, start: int, count: int):
+        """Rollouts start .. start+count-1 of query q: (rewards f32[count], lengths i32[count])."""
+        if start < 0 or count < 0 or start + count > self.max_per_query:
+            raise ValueError("rollout positions outside the simulator's range")
+        rng = _rng(self.seed, _S_SIM, 1 + int(q))
+        u = rng.random(self.max_per_query)
+        lengths = rng.integers(self.len_lo, self.len_hi + 1, size=self.max_per_query).astype(np.int32)
+        rewards = (u < self.p_q[q]).astype(np.float32)
+        return rewards[start:start + count], lengths[start:start + count]

@@ -62,3 +62,29 @@ def test_step_matches_checker(gh, mode):
     bound = 1e-2 * np.abs(ref["g"])[:, None] + np.abs(ref["dlogits"]) * 2.0 ** -23 + 1e-30
     assert (np.abs(got - ref["dlogits"]) <= bound).all()
     assert not got[ref["g"] == 0].any()
+
+
+@pytest.mark.parametrize("S", [0, 2])
+def test_allocated_groups_through_the_curation_kernel(gh, S):
+    """Groups that leave the two-stage allocation loop (ragged sizes 8..32, rescued pairs,
+    never-rescued queries) go through the curation kernel exactly as through the checker."""
+    from paper_2602_14338_amd.controller import allocate_rollouts
+    P = 96
+    sim = ai.RolloutSimulator(21 + S, P, beta=0.3)
+    alloc = allocate_rollouts(sim.draw, P, S=S)
+    keys = np.random.default_rng(S).integers(0, 2 ** 32, size=alloc.rewards.size, dtype=np.uint32)
+    params = dict(reject_enable=1, posterior_mode=1, s_rescue=S)
+    ref = orc.group_advantage(alloc.rewards, alloc.lengths, alloc.group_offsets, keys, OracleParams(**params))
+    out = gh.run_group_advantage((alloc.rewards, alloc.lengths, alloc.group_offsets, keys), params)
+    assert int(out["err"].item()) == 0
+    for key in ("keep_mask", "zero_var", "category", "kept_offsets"):
+        assert np.array_equal(out[key].cpu().numpy(), ref[key]), key
+    nk = int(ref["kept_offsets"][-1])
+    assert np.array_equal(out["kept_index"].cpu().numpy()[:nk], ref["kept_index"][:nk])
+    assert np.allclose(out["adv"].cpu().numpy(), ref["adv"], rtol=1e-6, atol=0)
+    assert np.allclose(out["weight"].cpu().numpy(), ref["weight"], rtol=1e-6, atol=0)
+    rescued = np.nonzero(alloc.rescued_at > 0)[0]
+    assert rescued.size
+    kept_per_query = np.diff(ref["kept_offsets"])
+    if S == 0:
+        assert np.array_equal(kept_per_query[rescued], 2 * alloc.c[rescued])
