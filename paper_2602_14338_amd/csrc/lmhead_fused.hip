@@ -49,7 +49,7 @@ struct FusedPlan {
 // dhidden is accumulated as S split-K partials of the active rows, S chosen on the device so
 // that (active token tiles) x (H tiles) x S fills the launch grid; the buffer holds S stacked
 // copies of the active rows, never more rows than the launch grid covers.
-constexpr int kDhGridMin = 1024;
+constexpr int kDhGridMin = 2048;
 static int dh_grid(int64_t T_pad, int H) {   // covers every tile even when all tokens are active
   const int tiles_h = (H + kTile - 1) / kTile;
   const int64_t all = (T_pad / kTile) * tiles_h;
@@ -549,18 +549,21 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 // ------------------------------------------------------------------------------------------
 // backward: the two gradient GEMMs
 // ------------------------------------------------------------------------------------------
-// Split-K factor for dhidden, from the number of active token tiles (uniform, device side):
-// the smallest S whose workgroup count base * S fills whole rounds of the 256 CUs best.
-__device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid) {
+// Split-K factor for dhidden, from the number of active token tiles (uniform, device side).
+// A workgroup's time is its share of the K slices plus a fixed tail (the read-modify-write of
+// its fp32 partial tile, worth about 16 slices of main loop); the launch takes
+// ceil(workgroups / 256) such rounds.  S minimises rounds x (slices / S + 16); `slices` is that
+// of a full vocabulary chunk for every chunk, so that all chunks use the same partial slots.
+__device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid, int slices) {
   const int base = active_tiles * tiles_h;
   if (base == 0) return 0;
   int best = 1;
-  float best_eff = 0.f;
-  for (int s = 1; base * s <= grid && s <= 64; ++s) {
-    const int wg = base * s;
-    const float eff = float(wg) / float((wg + 255) / 256 * 256);
-    if (eff > best_eff + 0.01f) {
-      best_eff = eff;
+  int64_t best_cost = INT64_MAX;
+  for (int s = 1; base * s <= grid && s <= 64 && s <= slices; ++s) {
+    const int64_t rounds = (int64_t(base) * s + 255) / 256;
+    const int64_t cost = rounds * ((slices + s - 1) / s + 16);
+    if (cost < best_cost) {
+      best_cost = cost;
       best = s;
     }
   }
@@ -569,13 +572,13 @@ __device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid
 
 // dh_part[s][t][h] (+)= sum_{k in split s} dz[t][k] W[v0 + k][h]   M = active tokens, N = H, K = vcK
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
-    const uint16_t* __restrict__ dz, const uint16_t* __restrict__ WT, int H_pad, int v0, int vcK,
+    const uint16_t* __restrict__ dz, const uint16_t* __restrict__ WT, int H_pad, int v0, int vcK, int plan_slices,
     int H, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, int accumulate,
     float* __restrict__ dh_part) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int n_pad = nact[1];
   const int tiles_t = n_pad / kTile;
-  const int S = dh_splits(tiles_t, tiles_h, gridDim.x);
+  const int S = dh_splits(tiles_t, tiles_h, gridDim.x, plan_slices);
   const int base = tiles_t * tiles_h;
   const int pid = blockIdx.x;
   if (S == 0 || pid >= base * S) return;   // uniform exit
@@ -646,7 +649,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
 // the partials are summed in split order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh_part, const int32_t* __restrict__ pos,
                                                     const int32_t* __restrict__ nact, int H, int tiles_h,
-                                                    int dh_grid, uint16_t* __restrict__ dhidden) {
+                                                    int dh_grid, int plan_slices, uint16_t* __restrict__ dhidden) {
   const int64_t t = blockIdx.x;
   const int j = pos[t];
   uint16_t* out = dhidden + t * H;
@@ -655,7 +658,7 @@ __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh
     return;
   }
   const int n_pad = nact[1];
-  const int S = dh_splits(n_pad / kTile, tiles_h, dh_grid);
+  const int S = dh_splits(n_pad / kTile, tiles_h, dh_grid, plan_slices);
   for (int k = threadIdx.x; k < H; k += 256) {
     float acc = 0.f;
     for (int s = 0; s < S; ++s) acc += dh_part[(int64_t(s) * n_pad + j) * H + k];
@@ -790,7 +793,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
       hipLaunchKernelGGL(k_fused_dz<false>, dim3(unsigned(tiles_vc * tiles_t)), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V,
                          H, v0, vc, tiles_vc, tiles_t, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
     hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(dh_grid(p.T_pad, H))), dim3(kGemmNT), kGemmLdsBytes, s, dz, WT,
-                       p.H_pad, v0, vcK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
+                       p.H_pad, v0, vcK, p.VC / kDK, H, tiles_h, p.T_pad, nact, chunk_no > 0 ? 1 : 0, dh_acc);
     if (dweight_dtype == AERO_BF16)
       hipLaunchKernelGGL((k_gemm_dw<true>), dim3(unsigned(tiles_vc * tiles_h)), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
                          hTc, p.VC, p.H_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
@@ -799,7 +802,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
                          hTc, p.VC, p.H_pad, v0, vc, H, tiles_vc, tiles_h, nact, dweight);
   }
   if (T > 0)
-    hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, nact, H, tiles_h, dh_grid(p.T_pad, H),
+    hipLaunchKernelGGL(k_scatter_dh, dim3(unsigned(T)), dim3(256), 0, s, dh_acc, pos, nact, H, tiles_h, dh_grid(p.T_pad, H), p.VC / kDK,
                        reinterpret_cast<uint16_t*>(dhidden));
   return launch_status();
 }
