@@ -69,8 +69,8 @@ static FusedPlan make_plan(int64_t T, int V, int H) {
   p.H = H;
   p.H_pad = int(up(size_t(H), kTile));
   p.tiles_v = p.V_ld / kTile;
-  // chunk so that dz and its transpose (T_pad x VC bf16 each) take at most 1 GiB each
-  int64_t vc = (int64_t(512) << 20) / p.T_pad / kTile * kTile;
+  // chunk so that dz and its transpose (T_pad x VC bf16 each) take at most 2 GiB each
+  int64_t vc = (int64_t(1024) << 20) / p.T_pad / kTile * kTile;
   if (vc < kTile) vc = kTile;
   if (vc > p.V_ld) vc = p.V_ld;
   p.VC = int(vc);
