@@ -23,7 +23,8 @@ aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld,
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, hipStream_t s);
+                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
+                        hipStream_t s);
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
@@ -31,12 +32,13 @@ struct LossWorkspace {
   float* loss_term;  // [T]
   int32_t* flag;     // [T] 0 = no signal, 1 = unclipped, 2 = clipped
   float* lse;        // [T] used when the caller gives none
-  float* lp_tmp;     // [T] sink for the forward pass's log-prob when lse is recomputed
+  float* lp_tmp;     // [T] sink for the forward pass's log-prob when lse is recomputed; the row order (i32) of
+                     //     the streaming single-pass kernel, which does not use that sink
   uint8_t* signal;   // [T] rows that carry signal, so the recomputing forward pass skips the rest
   float* ea;         // [T] entropy bonus: a_t = grad_scale c w
   float* eb;         // [T] entropy bonus: b_t = a_t (H_t - lse_t) - g_t
   float* ent;        // [T] entropy of the rows when the caller passes no array for it
-  int32_t* counter;  // [1] row counter of the streaming single-pass kernel
+  int32_t* counter;  // [3] counters of the streaming single-pass kernel
 };
 constexpr size_t kAlign = 256;
 inline size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
@@ -460,7 +462,8 @@ extern "C" aero_status aero_grpo_loss_bwd(
     if (!ent && single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
                                                 eps_lo, eps_hi, grad_scale, stats_all, ws.g, ws.loss_term, ws.flag,
-                                                logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter, s);
+                                                logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter,
+                                                reinterpret_cast<int32_t*>(ws.lp_tmp), s);
       if (sp != AERO_OK) return sp;
       hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
       return launch_status();

@@ -201,7 +201,10 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
 // The remaining NV - NL vectors are ordinary register loads issued at the top of a row.
 // Rows are handed out through a global counter (padding and zero-advantage rows cost far less
 // than gradient rows, a fixed stride would leave CUs idle); a workgroup always knows its next
-// row one row ahead, and leaves when the counter has passed T.
+// row one row ahead, and leaves when the counter has passed T.  The counter indexes a row order
+// in which the rows that are read come first and the rows that are only zero-filled last
+// (k_row_order): the memory system then sees a read+write phase followed by a write-only
+// phase instead of a mix of the two, which is worth several percent on padded batches.
 // ------------------------------------------------------------------------------------------
 struct RowInfo {
   int y;
@@ -226,6 +229,29 @@ __device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, 
   return r;
 }
 
+// order[0 .. n) = rows with need, order[n .. T) = the others, each part in no particular order
+// (wave-sized runs are placed by two atomic counters: ctr[1] from the front, ctr[2] from the back).
+__global__ __launch_bounds__(256) void k_row_order(int64_t T, int V, int R, const int32_t* __restrict__ targets,
+                                                   const int32_t* __restrict__ token_rollout,
+                                                   const float* __restrict__ adv, const float* __restrict__ weight,
+                                                   int stats_all, int32_t* __restrict__ ctr, int32_t* __restrict__ order) {
+  const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const bool in = t < T;
+  const bool need = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all).need;
+  const uint64_t m_need = __ballot(in && need), m_rest = __ballot(in && !need);
+  const uint64_t below = (uint64_t(1) << lane) - 1;
+  int base_need = 0, base_rest = 0;
+  if (lane == 0) {
+    if (m_need) base_need = atomicAdd(ctr + 1, __popcll(m_need));
+    if (m_rest) base_rest = atomicAdd(ctr + 2, __popcll(m_rest));
+  }
+  base_need = __shfl(base_need, 0, kWave);
+  base_rest = __shfl(base_rest, 0, kWave);
+  if (in && need) order[base_need + __popcll(m_need & below)] = int32_t(t);
+  if (in && !need) order[T - 1 - (base_rest + __popcll(m_rest & below))] = int32_t(t);
+}
+
 template <int NV, int NL>
 __global__ __launch_bounds__(kSpNT) void k_row_stream(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
@@ -233,7 +259,8 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
     float grad_scale, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
-    float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter) {
+    float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter,
+    const int32_t* __restrict__ order) {
   __shared__ RowStat lds[2][kSpNT / kWave];   // alternating: one barrier per row is enough
   __shared__ int s_next;
   extern __shared__ __align__(16) u32x4_t slots_raw[];   // NL x kSpNT vectors
@@ -255,11 +282,13 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
                                              voff + uint32_t(u) * (kSpNT * 16u), 0, 0, 2);
   };
 
-  // the first gridDim.x rows are assigned by workgroup id; the counter starts at gridDim.x
-  int64_t t = blockIdx.x;
+  // the first gridDim.x positions of the row order are assigned by workgroup id; the counter
+  // starts at gridDim.x.  pn = position of the next row, tn = that row (T = none left)
+  int64_t t = order[blockIdx.x];
   if (tid == 0) s_next = atomicAdd(row_counter, 1);
   __syncthreads();
-  int64_t tn = s_next;
+  int64_t pn = s_next;
+  int64_t tn = pn < T ? order[pn] : T;
   RowInfo cur = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all);
   if (cur.need) {
     const __amdgpu_buffer_rsrc_t src = row_rsrc(logits, t);
@@ -404,15 +433,22 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     }
     // hand-over: the row after the next one is drawn now (all threads have read s_next)
     __syncthreads();
-    if (tid == 0) s_next = tn < T ? atomicAdd(row_counter, 1) : int(T);
+    if (tid == 0) s_next = pn < T ? atomicAdd(row_counter, 1) : int(T);
     __syncthreads();
     cur = nxt;
     t = tn;
-    tn = s_next;
+    pn = s_next;
+    tn = pn < T ? order[pn] : T;
   }
 }
 
-__global__ void k_set_counter(int32_t* p, int32_t v) { *p = v; }
+// ctr[0]: row counter of k_row_stream (starts past the rows assigned by workgroup id),
+// ctr[1], ctr[2]: fill counters of k_row_order
+__global__ void k_set_counter(int32_t* ctr, int32_t v) {
+  ctr[0] = v;
+  ctr[1] = 0;
+  ctr[2] = 0;
+}
 
 // True when the single-pass kernel applies: bf16, 16-byte aligned rows, and a row that fits
 // the register budget of one 1024-thread workgroup.
@@ -426,7 +462,8 @@ aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld,
                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
                         float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, hipStream_t s) {
+                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
+                        hipStream_t s) {
   const uint16_t* z = reinterpret_cast<const uint16_t*>(logits);
   uint16_t* dz = reinterpret_cast<uint16_t*>(dlogits);
   if (V / 8 <= 8 * kSpNT)
@@ -451,9 +488,11 @@ aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld,
     }
     const unsigned grid = unsigned(T < cus ? T : cus);   // one persistent workgroup per CU
     hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(1), 0, s, row_counter, int32_t(grid));
+    hipLaunchKernelGGL(k_row_order, dim3(unsigned((T + 255) / 256)), dim3(256), 0, s, T, V, R, targets, token_rollout,
+                       adv, weight, stats_all, row_counter, row_order);
     hipLaunchKernelGGL((k_row_stream<20, NL>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets, old_logprob,
                        token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
-                       logprob_out, entropy_out, lse_out, dz, err_flag, row_counter);
+                       logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);
   }
   return AERO_OK;
 }
