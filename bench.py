@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
 # WRITE_SIZE, each scaled by what the same counter reads for an elementwise copy of known size;
 # see profiles/logits_path_cfg2_hbm_traffic.txt).  Valid only for the kernel sources it was
 # measured on: the figure is reported only while their hash still matches.
-MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8587e+09, "sources_sha256": "3f9f5d4c101aacf98c697eaa2878bae8568d22a84be8708614486fa7d5e0c59b"}}
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8596e+09, "sources_sha256": "4606cf89422eed9f01e66d83e1f66c5666ef6affe738f31959694b8a8be94cef"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
 
 
@@ -260,7 +260,7 @@ def main():
                        "two_call_logprob_fwd": ms_fwd, "two_call_grpo_loss_bwd": ms_bwd},
         "two_call_route": {"tokens_per_s": n_valid * K / wall2, "ms_per_step": wall2 / K * 1e3,
                            "logprob_fwd_GBps": fwd_gbs, "dlogits_GBps": bwd_gbs},
-        "roofline": {"kernel": "k_row_stream (timed as the whole aero_grpo_loss_bwd call: counter preset + k_row_stream + loss reduce)", "bound": "hbm",
+        "roofline": {"kernel": "k_row_stream (timed as the whole aero_grpo_loss_bwd call: counter preset + row order + k_row_stream + loss reduce)", "bound": "hbm",
                      "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": single_gbs / HBM_PEAK_GBS,
                      "algorithmic_bytes": single_bytes, "traffic": measured_traffic(name)},
     }
