@@ -232,30 +232,32 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_stats(
   }
 }
 
-// 64 consecutive compact rows per workgroup.  Phase 1: lane <-> row, the tiles_v partials are
-// split over the four waves (every load is one coalesced 256-byte row segment) and merged
-// through LDS.  Phase 2: each wave takes 16 of the rows and computes the sampled token's logit
+// 64 consecutive compact rows per workgroup of 16 waves.  Phase 1: lane <-> row, the tiles_v
+// partials are split over the waves (every load is one coalesced 256-byte row segment) and merged
+// through LDS.  Phase 2: each wave takes 4 of the rows and computes the sampled token's logit
 // as a dot product of the two bf16 rows; results go to the row's original position.
 constexpr int kCombineTokens = 64;
-__global__ __launch_bounds__(256) void k_fused_combine(
+constexpr int kCombineWaves = 16;
+__global__ __launch_bounds__(kCombineWaves * kWave) void k_fused_combine(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hf, int H, int tiles_v, int64_t T_pad,
     const int32_t* __restrict__ fidx, const int32_t* __restrict__ nf, const float* __restrict__ part_m,
     const float* __restrict__ part_s, const float* __restrict__ part_sz, const int32_t* __restrict__ targets,
     float* __restrict__ logprob, float* __restrict__ entropy, float* __restrict__ lse_out) {
-  __shared__ RowStat xs[4][kCombineTokens];
+  __shared__ RowStat xs[kCombineWaves][kCombineTokens];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t j0 = int64_t(blockIdx.x) * kCombineTokens;   // j0 + 63 < T_pad
   const int n = nf[0];
   if (j0 >= n) return;
   RowStat st = stat_identity();
-  for (int tv = wave; tv < tiles_v; tv += 4) {
+  for (int tv = wave; tv < tiles_v; tv += kCombineWaves) {
     const int64_t o = int64_t(tv) * T_pad + j0 + lane;
     st = stat_merge(st, RowStat{part_m[o], part_s[o], part_sz[o]});
   }
   xs[wave][lane] = st;
   __syncthreads();
-  for (int k16 = 0; k16 < kCombineTokens / 4; ++k16) {
-    const int c = wave * (kCombineTokens / 4) + k16;
+  constexpr int kPerWave = kCombineTokens / kCombineWaves;
+  for (int k4 = 0; k4 < kPerWave; ++k4) {
+    const int c = wave * kPerWave + k4;
     const int64_t j = j0 + c;
     if (j >= n) break;   // uniform per wave
     const int64_t t = fidx[j];
@@ -272,8 +274,11 @@ __global__ __launch_bounds__(256) void k_fused_combine(
     }
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+    // the 16 wave partials of this row, merged by a 16-lane tree in a fixed order
+    RowStat r = lane < kCombineWaves ? xs[lane][c] : stat_identity();
+#pragma unroll
+    for (int off = kCombineWaves / 2; off > 0; off >>= 1) r = stat_merge(r, stat_shfl_xor(r, off));
     if (lane == 0) {
-      const RowStat r = stat_merge(stat_merge(xs[0][c], xs[1][c]), stat_merge(xs[2][c], xs[3][c]));
       const float lse = r.m + logf(r.s);
       logprob[t] = dot - lse;
       lse_out[t] = lse;
@@ -736,7 +741,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     hipLaunchKernelGGL(k_gather_rows, dim3(unsigned(p.T_pad / 4)), dim3(256), 0, s, Hp, H, fidx, p.T_pad, hf);
     hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(p.tiles_v * tiles_t)), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hf,
                        V, H, p.tiles_v, tiles_t, p.T_pad, nf, part_m, part_s, part_sz);
-    hipLaunchKernelGGL(k_fused_combine, dim3(unsigned(p.T_pad / kCombineTokens)), dim3(256), 0, s, Wp, hf, H,
+    hipLaunchKernelGGL(k_fused_combine, dim3(unsigned(p.T_pad / kCombineTokens)), dim3(kCombineWaves * kWave), 0, s, Wp, hf, H,
                        p.tiles_v, p.T_pad, fidx, nf, part_m, part_s, part_sz, targets, logprob, ent_arr, lse);
   }
   if (!bwd) return launch_status();
