@@ -134,7 +134,6 @@ aero_status aero_logprob_fwd(
  * entropy_coef = c != 0 every token of a rollout with w != 0, whatever A or the clip decision,
  *     loss -= c * w * H_t,   dlogits[t, j] += grad_scale * c * w * p_j * (ln p_j + H_t),
  *     p_j = exp(z[t,j] - lse[t]), H_t = entropy of row t.
- * With c != 0 the statistics-and-gradient call is two passes over HBM (6 bytes per logit).
  *
  * logits / dlogits  [T, ld], same dtype and ld; dlogits may alias logits (in place).
  * lse      f32[T] from aero_logprob_fwd, or NULL: then the statistics are computed here.  With

@@ -20,11 +20,11 @@ aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int
                                float* entropy, float* lse, int32_t* err_flag, hipStream_t s);
 bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits, const void* dlogits);
 aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
-                        const float* old_logprob, const int32_t* token_rollout, const float* adv,
-                        const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
-                        float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
-                        hipStream_t s);
+                               const float* old_logprob, const int32_t* token_rollout, const float* adv,
+                               const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
+                               float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
+                               float* logprob_out, float* entropy_out, float* lse_out, void* dlogits,
+                               int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s);
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
@@ -459,9 +459,10 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (!lse) {
     // statistics are computed here; with entropy_out / lse_out they cover every valid row
     const int stats_all = (entropy_out || lse_out) ? 1 : 0;
-    if (!ent && single_pass_applicable(dtype, V, ld, logits, dlogits)) {
+    if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
-                                                eps_lo, eps_hi, grad_scale, stats_all, ws.g, ws.loss_term, ws.flag,
+                                                eps_lo, eps_hi, grad_scale, entropy_coef, stats_all, ws.g, ws.loss_term,
+                                                ws.flag,
                                                 logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter,
                                                 reinterpret_cast<int32_t*>(ws.lp_tmp), s);
       if (sp != AERO_OK) return sp;

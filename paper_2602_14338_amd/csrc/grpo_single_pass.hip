@@ -16,12 +16,13 @@ constexpr int kSpNT = 1024;
 // (filled directly by buffer_load ... lds, each lane reads back only what its own wave loaded),
 // because 20 x 4 data registers plus the working set exceed the 128 VGPRs a 1024-thread
 // workgroup may use and the overflow would otherwise go to scratch memory in HBM.
-template <int NV, int NL>
+// ENT: the entropy-bonus term is part of the loss and of the gradient row.
+template <int NV, int NL, bool ENT>
 __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
-    float grad_scale, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
+    float grad_scale, float ent_coef, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag) {
   __shared__ RowStat lds[kSpNT / kWave];
@@ -39,7 +40,8 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     w = weight[i];
   }
   const bool signal = valid && A != 0.f && w != 0.f;
-  const bool need = signal || (valid && stats_all);   // uniform over the workgroup
+  const bool bonus = ENT && valid && w != 0.f;          // entropy bonus: every token of a weighted rollout
+  const bool need = signal || bonus || (valid && stats_all);   // uniform over the workgroup
   const size_t row_off = size_t(t) * size_t(ld);
   const uint16_t* zrow = logits + row_off;
   uint16_t* drow = dlogits ? dlogits + row_off : nullptr;
@@ -134,23 +136,30 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     g = unclipped ? -grad_scale * w * A * rho : 0.f;
     flag = unclipped ? 1 : 2;
   }
+  const float ent = lse - st.sz / st.s;
+  // gradient row: dz_j = pi_j (a z_j + b) + g 1[j = y]; without the entropy bonus a = 0, b = -g
+  float a = 0.f, ng = -g;
+  if (bonus) {
+    term -= ent_coef * w * ent;
+    a = grad_scale * ent_coef * w;
+    ng = a * (ent - lse) - g;
+  }
   if (tid == 0) {
     g_out[t] = g;
     term_out[t] = term;
     flag_out[t] = flag;
     if (logprob_out) logprob_out[t] = lp;
-    if (entropy_out) entropy_out[t] = lse - st.sz / st.s;
+    if (entropy_out) entropy_out[t] = ent;
     if (lse_out) lse_out[t] = lse;
   }
   if (!drow) return;
-  if (g == 0.f) {
+  if (g == 0.f && a == 0.f) {
     zero_fill();
     return;
   }
 
   // ---- gradient row from the registers ----
   const float c = -lse * kLog2e;
-  const float ng = -g;
   const __amdgpu_buffer_rsrc_t dsrc = __builtin_amdgcn_make_buffer_rsrc(drow, 0, nvec * 16, 0x00020000);
   // the store offsets are formed again from an opaque copy of the lane offset; otherwise the
   // compiler keeps all NV load offsets alive across the reduction just to reuse them here
@@ -171,7 +180,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
       }
       unpack8(src, z);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
+      for (int e = 0; e < 8; ++e) d[e] = (ENT ? fmaf(a, z[e], ng) : ng) * exp2_fast(fmaf(z[e], kLog2e, c));
       if (k == yvec) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
@@ -186,7 +195,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     __builtin_amdgcn_sched_barrier(0);
   }
   if (has_tail) {
-    float d = ng * exp2_fast(fmaf(ztail, kLog2e, c));
+    float d = (ENT ? fmaf(a, ztail, ng) : ng) * exp2_fast(fmaf(ztail, kLog2e, c));
     if (jt == y) d += g;
     drow[jt] = f32_to_bf16(d);
   }
@@ -209,13 +218,14 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
 struct RowInfo {
   int y;
   float A, w;
-  bool valid, signal, need;
+  bool valid, signal, bonus, need;
 };
 
+// every_weighted: the entropy bonus is on, rows of weighted rollouts with advantage 0 count too
 __device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, const int32_t* targets,
                                             const int32_t* token_rollout, const float* adv, const float* weight,
-                                            int stats_all) {
-  RowInfo r{0, 0.f, 0.f, false, false, false};
+                                            int stats_all, bool every_weighted) {
+  RowInfo r{0, 0.f, 0.f, false, false, false, false};
   if (t >= T) return r;
   const int i = token_rollout[t];
   r.y = targets[t];
@@ -225,7 +235,8 @@ __device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, 
     r.w = weight[i];
   }
   r.signal = r.valid && r.A != 0.f && r.w != 0.f;
-  r.need = r.signal || (r.valid && stats_all);
+  r.bonus = every_weighted && r.valid && r.w != 0.f;
+  r.need = r.signal || r.bonus || (r.valid && stats_all);
   return r;
 }
 
@@ -234,11 +245,12 @@ __device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, 
 __global__ __launch_bounds__(256) void k_row_order(int64_t T, int V, int R, const int32_t* __restrict__ targets,
                                                    const int32_t* __restrict__ token_rollout,
                                                    const float* __restrict__ adv, const float* __restrict__ weight,
-                                                   int stats_all, int32_t* __restrict__ ctr, int32_t* __restrict__ order) {
+                                                   int stats_all, int every_weighted, int32_t* __restrict__ ctr,
+                                                   int32_t* __restrict__ order) {
   const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
   const int lane = threadIdx.x & 63;
   const bool in = t < T;
-  const bool need = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all).need;
+  const bool need = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all, every_weighted != 0).need;
   const uint64_t m_need = __ballot(in && need), m_rest = __ballot(in && !need);
   const uint64_t below = (uint64_t(1) << lane) - 1;
   int base_need = 0, base_rest = 0;
@@ -252,12 +264,12 @@ __global__ __launch_bounds__(256) void k_row_order(int64_t T, int V, int R, cons
   if (in && !need) order[T - 1 - (base_rest + __popcll(m_rest & below))] = int32_t(t);
 }
 
-template <int NV, int NL>
+template <int NV, int NL, bool ENT>
 __global__ __launch_bounds__(kSpNT) void k_row_stream(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
-    float grad_scale, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
+    float grad_scale, float ent_coef, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter,
     const int32_t* __restrict__ order) {
@@ -289,7 +301,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
   __syncthreads();
   int64_t pn = s_next;
   int64_t tn = pn < T ? order[pn] : T;
-  RowInfo cur = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all);
+  RowInfo cur = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all, ENT);
   if (cur.need) {
     const __amdgpu_buffer_rsrc_t src = row_rsrc(logits, t);
 #pragma unroll
@@ -298,11 +310,12 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
 
   int reduces = 0;   // selects the LDS buffer of the next reduction
   while (t < T) {
-    const RowInfo nxt = row_info(tn, T, V, R, targets, token_rollout, adv, weight, stats_all);
+    const RowInfo nxt = row_info(tn, T, V, R, targets, token_rollout, adv, weight, stats_all, ENT);
     const uint16_t* zrow = logits + size_t(t) * size_t(ld);
     uint16_t* drow = dlogits ? dlogits + size_t(t) * size_t(ld) : nullptr;
     const __amdgpu_buffer_rsrc_t nsrc = row_rsrc(logits, nxt.need ? tn : t);
     float g = 0.f, term = 0.f, lp = 0.f, ent = 0.f, lse = 0.f;
+    float ea = 0.f;   // entropy bonus: grad_scale c w of this row (ENT only)
     int flag = 0;
     u32x4_t v[NR];
     float ztail = 0.f;
@@ -360,6 +373,12 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
         g = unclipped ? -grad_scale * cur.w * cur.A * rho : 0.f;
         flag = unclipped ? 1 : 2;
       }
+      if constexpr (ENT) {
+        if (cur.bonus) {
+          term -= ent_coef * cur.w * ent;
+          ea = grad_scale * ent_coef * cur.w;
+        }
+      }
     }
     if (tid == 0) {
       if (!cur.valid && err_flag) {
@@ -374,9 +393,11 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
       if (lse_out) lse_out[t] = lse;
     }
 
-    if (drow && g != 0.f) {
+    if (drow && (g != 0.f || (ENT && ea != 0.f))) {
       const float c = -lse * kLog2e;
-      const float ng = -g;
+      // gradient row: dz_j = pi_j (a z_j + ng) + g 1[j = y]; without the entropy bonus a = 0, ng = -g
+      const float a = ea;
+      const float ng = ENT ? ea * (ent - lse) - g : -g;
       const __amdgpu_buffer_rsrc_t dsrc = row_rsrc(dlogits, t);
       uint32_t voff_st = voff;   // opaque copy: keeps the load offsets from being kept alive for reuse
       asm volatile("" : "+v"(voff_st));
@@ -385,7 +406,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
         float z[8], d[8];
         unpack8(src, z);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d[e] = ng * exp2_fast(fmaf(z[e], kLog2e, c));
+        for (int e = 0; e < 8; ++e) d[e] = (ENT ? fmaf(a, z[e], ng) : ng) * exp2_fast(fmaf(z[e], kLog2e, c));
         if (k == yvec) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
@@ -413,7 +434,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
         __builtin_amdgcn_sched_barrier(0);
       }
       if (has_tail) {
-        float d = ng * exp2_fast(fmaf(ztail, kLog2e, c));
+        float d = (ENT ? fmaf(a, ztail, ng) : ng) * exp2_fast(fmaf(ztail, kLog2e, c));
         if (jt == y) d += g;
         drow[jt] = f32_to_bf16(d);
       }
@@ -458,43 +479,60 @@ bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits
          reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0;
 }
 
+template <bool ENT>
+static aero_status single_pass_launch_t(const uint16_t* z, int64_t T, int V, int64_t ld, const int32_t* targets,
+                                        const float* old_logprob, const int32_t* token_rollout, const float* adv,
+                                        const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
+                                        float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
+                                        float* logprob_out, float* entropy_out, float* lse_out, uint16_t* dz,
+                                        int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s) {
+  if (V / 8 <= 8 * kSpNT) {
+    hipLaunchKernelGGL((k_row_single_pass<8, 0, ENT>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets,
+                       old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, stats_all, g,
+                       term, flag, logprob_out, entropy_out, lse_out, dz, err_flag);
+    return AERO_OK;
+  }
+  constexpr int NL = 9;
+  constexpr int kLdsBytes = NL * kSpNT * 16;   // 144 KB of wave-private slots
+  // raising the dynamic-LDS limit is per function; done once per process, safely from any thread
+  static std::once_flag attr_once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(attr_once, [] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(k_row_stream<20, NL, ENT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  });
+  if (attr_rc != hipSuccess) return AERO_ERR_HIP;
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+  }
+  const unsigned grid = unsigned(T < cus ? T : cus);   // one persistent workgroup per CU
+  hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(1), 0, s, row_counter, int32_t(grid));
+  hipLaunchKernelGGL(k_row_order, dim3(unsigned((T + 255) / 256)), dim3(256), 0, s, T, V, R, targets, token_rollout,
+                     adv, weight, stats_all, ENT ? 1 : 0, row_counter, row_order);
+  hipLaunchKernelGGL((k_row_stream<20, NL, ENT>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets,
+                     old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, stats_all, g,
+                     term, flag, logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);
+  return AERO_OK;
+}
+
+// ent_coef != 0 selects the kernels that carry the entropy-bonus term.
 aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
-                        const float* old_logprob, const int32_t* token_rollout, const float* adv,
-                        const float* weight, int R, float eps_lo, float eps_hi, float grad_scale, int stats_all,
-                        float* g, float* term, int32_t* flag, float* logprob_out, float* entropy_out,
-                        float* lse_out, void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
-                        hipStream_t s) {
+                               const float* old_logprob, const int32_t* token_rollout, const float* adv,
+                               const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
+                               float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
+                               float* logprob_out, float* entropy_out, float* lse_out, void* dlogits,
+                               int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s) {
   const uint16_t* z = reinterpret_cast<const uint16_t*>(logits);
   uint16_t* dz = reinterpret_cast<uint16_t*>(dlogits);
-  if (V / 8 <= 8 * kSpNT)
-    hipLaunchKernelGGL((k_row_single_pass<8, 0>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets, old_logprob,
-                       token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
-                       logprob_out, entropy_out, lse_out, dz, err_flag);
-  else {
-    constexpr int NL = 9;
-    constexpr int kLdsBytes = NL * kSpNT * 16;   // 144 KB of wave-private slots
-    // raising the dynamic-LDS limit is per function; done once per process, safely from any thread
-    static std::once_flag attr_once;
-    static hipError_t attr_rc = hipSuccess;
-    std::call_once(attr_once, [] {
-      attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(k_row_stream<20, NL>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    });
-    if (attr_rc != hipSuccess) return AERO_ERR_HIP;
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) {
-      int n = 0;
-      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-    }
-    const unsigned grid = unsigned(T < cus ? T : cus);   // one persistent workgroup per CU
-    hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(1), 0, s, row_counter, int32_t(grid));
-    hipLaunchKernelGGL(k_row_order, dim3(unsigned((T + 255) / 256)), dim3(256), 0, s, T, V, R, targets, token_rollout,
-                       adv, weight, stats_all, row_counter, row_order);
-    hipLaunchKernelGGL((k_row_stream<20, NL>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets, old_logprob,
-                       token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, stats_all, g, term, flag,
-                       logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);
-  }
-  return AERO_OK;
+  if (ent_coef != 0.f)
+    return single_pass_launch_t<true>(z, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                                      grad_scale, ent_coef, stats_all, g, term, flag, logprob_out, entropy_out,
+                                      lse_out, dz, err_flag, row_counter, row_order, s);
+  return single_pass_launch_t<false>(z, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                                     grad_scale, 0.f, stats_all, g, term, flag, logprob_out, entropy_out, lse_out, dz,
+                                     err_flag, row_counter, row_order, s);
 }
 
 }  // namespace aero

@@ -704,6 +704,8 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   if (size_t(p.H_pad) * size_t(p.T_pad) * 2 >= kOperandLimit || size_t(p.H_pad) * size_t(p.VC) * 2 >= kOperandLimit ||
       size_t(p.T_pad) * size_t(p.VC) * 2 >= kOperandLimit)
     return AERO_ERR_SHAPE;
+  // one workgroup per 256 x 256 tile: the tile count must fit a launch grid
+  if (int64_t(p.tiles_v) * (p.T_pad / kTile) >= (int64_t(1) << 31)) return AERO_ERR_SHAPE;
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kWsAlign || workspace_bytes < p.total)
     return AERO_ERR_WORKSPACE;
   hipStream_t s = as_stream(stream);
