@@ -519,7 +519,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const int u = threadIdx.x + k * kGemmNT;
     const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
     const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
-    *reinterpret_cast<u32x4_t*>(dz + (int64_t(m0 / 64 + sl) * T_pad + n0 + r) * 64 + c8 * 8) = val;
+    __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dz + (int64_t(m0 / 64 + sl) * T_pad + n0 + r) * 64 + c8 * 8));
   }
   __syncthreads();
   // ---- [vocab][token]: neighbouring lanes swap halves so that each writes one (t, t+1) pair ----
@@ -547,7 +547,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const int u = threadIdx.x + k * kGemmNT;
     const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
     const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
-    *reinterpret_cast<u32x4_t*>(dzT + (int64_t(n0 / 64 + sl) * VC + m0 + r) * 64 + c8 * 8) = val;
+    __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dzT + (int64_t(n0 / 64 + sl) * VC + m0 + r) * 64 + c8 * 8));
   }
 }
 
@@ -613,8 +613,10 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
+        // partials are touched once per vocabulary chunk: streamed past the caches
         float* p = out + int64_t(m0 + acc_row(wm, mb, i, lane)) * H + col;
-        *p = accumulate ? *p + acc[mb][nb][i] : acc[mb][nb][i];
+        const float prev = accumulate ? __builtin_nontemporal_load(p) : 0.f;
+        __builtin_nontemporal_store(prev + acc[mb][nb][i], p);
       }
   }
 }
@@ -643,8 +645,9 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
         const int row = m0 + acc_row(wm, mb, i, lane);
         if (row < vc) {
           const int64_t o = int64_t(v0 + row) * H + col;
-          if constexpr (OUT_BF16) reinterpret_cast<uint16_t*>(dW)[o] = f32_to_bf16(acc[mb][nb][i]);
-          else reinterpret_cast<float*>(dW)[o] = acc[mb][nb][i];
+          // the gradient is not read again by this call: keep it out of the caches
+          if constexpr (OUT_BF16) __builtin_nontemporal_store(f32_to_bf16(acc[mb][nb][i]), reinterpret_cast<uint16_t*>(dW) + o);
+          else __builtin_nontemporal_store(acc[mb][nb][i], reinterpret_cast<float*>(dW) + o);
         }
       }
   }
