@@ -18,7 +18,7 @@ in float64, step by step as the paper states it:
   logprob_fwd       App. C softmax policy; log-prob of the sampled token; entropy.
   grpo_loss_bwd     Eq. 2 clipped surrogate (beta = 0) and its gradient w.r.t. the
                     logits, App. A.1 (gradient of the ratio, clipped tokens give zero);
-                    optional entropy bonus (Table 8 coefficient).
+                    optional entropy bonus (Table 8 coefficient) and KL penalty (Eq. 2's beta term).
   lmhead_fused      the same, with logits defined as hidden @ weight^T.
 
 Readings of points the paper leaves open are listed next to the code that takes
@@ -26,7 +26,8 @@ them.  Two of them have no external pin ("parity unpinned"): in posterior mode t
 standard deviation that divides (r - u~) is taken as sqrt(u~ (1 - u~)); and the entropy
 bonus, for which the paper gives a coefficient only, is aggregated with the weights of
 Eq. 2 over every token of a weighted rollout (the entropy and its gradient themselves are
-pinned).
+pinned).  A third reading of that kind: Eq. 2's KL penalty is evaluated with the per-token
+estimator exp(d) - d - 1 of the GRPO literature (the paper names none and trains with beta = 0).
 """
 from __future__ import annotations
 
@@ -240,7 +241,8 @@ def entropy_grad_row(z: np.ndarray, lse: float, ent: float) -> np.ndarray:
 def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old_logprob,
                   token_rollout, adv, weight, eps_lo: float, eps_hi: float,
                   grad_scale: float = 1.0, want_dlogits: bool = True,
-                  z64: Optional[np.ndarray] = None, entropy_coef: float = 0.0):
+                  z64: Optional[np.ndarray] = None, entropy_coef: float = 0.0,
+                  kl_coef: float = 0.0, ref_logprob=None):
     """loss = - sum_t w_{i(t)} s_t over tokens of kept rollouts, and dlogits.
 
     A row contributes nothing, and its gradient row is exactly +0, when it is padding
@@ -256,6 +258,12 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
     loss -= c w H_t  and  dlogits[t, j] += - grad_scale c w dH_t/dz_j
                                          = grad_scale c w pi_j (ln pi_j + H_t).
 
+    KL penalty (the - beta D_KL(pi_theta || pi_ref) term inside Eq. 2's token sum; the paper names
+    no estimator, the per-token one of the GRPO literature is taken): with kl_coef = beta != 0,
+    for every token of a rollout with w != 0 (clipped or not, App. A.1),
+        D_t = exp(d) - d - 1,  d = ref_logprob[t] - log pi(y_t)          (>= 0, 0 iff d = 0)
+        loss += beta w D_t,    g_t += grad_scale beta w (1 - exp(d))     (d D_t / d log pi = 1 - exp(d)).
+
     ``z64`` may supply the logits already in float64 ([T, V]) instead of ``logits``.
     """
     T = len(targets)
@@ -263,7 +271,9 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
     weight = np.asarray(weight, np.float64)
     old_logprob = np.asarray(old_logprob, np.float64)
     eps_lo, eps_hi, grad_scale = float(eps_lo), float(eps_hi), float(grad_scale)
-    c_ent = float(entropy_coef)
+    c_ent, beta = float(entropy_coef), float(kl_coef)
+    if beta != 0.0:
+        ref_logprob = np.asarray(ref_logprob, np.float64)
     loss = 0.0
     g = np.zeros(T)
     e = np.zeros(T)
@@ -273,7 +283,7 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
     n_signal = n_clipped = 0
     for t in range(T):
         i, y = int(token_rollout[t]), int(targets[t])
-        if i < 0 or y < 0 or weight[i] == 0.0 or (adv[i] == 0.0 and c_ent == 0.0):
+        if i < 0 or y < 0 or weight[i] == 0.0 or (adv[i] == 0.0 and c_ent == 0.0 and beta == 0.0):
             continue
         z = z64[t] if z64 is not None else widen(logits[t, :V], dtype)
         lp[t], ent, lse = logprob_row(z, y)
@@ -282,6 +292,10 @@ def grpo_loss_bwd(logits: Optional[np.ndarray], dtype: str, V: int, targets, old
                                                             eps_lo, eps_hi, grad_scale)
             n_signal += 1
             n_clipped += 0 if unclipped else 1
+        if beta != 0.0:
+            d = ref_logprob[t] - lp[t]
+            loss_terms[t] += beta * weight[i] * (np.exp(d) - d - 1.0)
+            g[t] += grad_scale * beta * weight[i] * (1.0 - np.exp(d))
         if c_ent != 0.0:
             loss_terms[t] -= c_ent * weight[i] * ent
             e[t] = grad_scale * c_ent * weight[i]
@@ -306,7 +320,8 @@ def lmhead_logits(hidden_bits: np.ndarray, weight_bits: np.ndarray) -> np.ndarra
 
 
 def lmhead_fused(hidden_bits, weight_bits, targets, old_logprob=None, token_rollout=None,
-                 adv=None, weight=None, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0, entropy_coef=0.0):
+                 adv=None, weight=None, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0, entropy_coef=0.0,
+                 kl_coef=0.0, ref_logprob=None):
     """Forward statistics of the product logits and, when the loss inputs are given, the
     loss and the gradients dhidden = dz W and dweight = dz^T h with the unrounded dz."""
     z = lmhead_logits(hidden_bits, weight_bits)
@@ -320,7 +335,8 @@ def lmhead_fused(hidden_bits, weight_bits, targets, old_logprob=None, token_roll
     out = dict(logprob=lp, entropy=ent, lse=lse)
     if old_logprob is not None:
         b = grpo_loss_bwd(None, "f64", V, targets, old_logprob, token_rollout, adv, weight,
-                          eps_lo, eps_hi, grad_scale, want_dlogits=True, z64=z, entropy_coef=entropy_coef)
+                          eps_lo, eps_hi, grad_scale, want_dlogits=True, z64=z, entropy_coef=entropy_coef,
+                          kl_coef=kl_coef, ref_logprob=ref_logprob)
         dz = b["dlogits"]
         out.update(loss=b["loss"], clip_frac=b["clip_frac"], g=b["g"], e=b["e"], loss_terms=b["loss_terms"],
                    dhidden=dz @ widen(weight_bits, "bf16"),

@@ -437,6 +437,65 @@ def test_entropy_gradient_closed_forms_and_central_differences():
     assert not orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(R), w, 0.2, 0.2, z64=zz)["dlogits"].any()
 
 
+# ------------------------------------------------------------------ KL penalty (Eq. 2, beta term)
+
+@pytest.mark.parametrize("seed", range(4))
+def test_kl_penalty_matches_autograd(seed):
+    z, y, tr, adv, w, old = tiny_problem(300 + seed)
+    w[1] = 0.0
+    tr[0], tr[1] = 0, 1                            # rollout 0 has advantage 0, rollout 1 weight 0
+    rng = np.random.default_rng(seed)
+    ref_lp = old + rng.normal(0, 0.2, size=old.shape)
+    beta = 0.04
+    out = orc.grpo_loss_bwd(None, "f64", z.shape[1], y, old, tr, adv, w, 0.2, 0.2, grad_scale=2.0, z64=z,
+                            kl_coef=beta, ref_logprob=ref_lp, entropy_coef=0.01)
+    zt = torch.tensor(z, dtype=torch.float64, requires_grad=True)
+    lp = torch.log_softmax(zt, dim=1).gather(1, torch.tensor(y, dtype=torch.int64)[:, None])[:, 0]
+    rho = torch.exp(lp - torch.tensor(old))
+    A = torch.tensor(adv)[torch.tensor(tr, dtype=torch.int64)]
+    W = torch.tensor(w)[torch.tensor(tr, dtype=torch.int64)]
+    s = torch.minimum(rho * A, torch.clamp(rho, 0.8, 1.2) * A)
+    d = torch.tensor(ref_lp) - lp
+    kl = torch.exp(d) - d - 1
+    H = torch.distributions.Categorical(logits=zt).entropy()
+    loss = -(W * s).sum() + beta * (W * kl).sum() - 0.01 * (W * H).sum()
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-13
+    assert np.allclose(out["dlogits"], 2.0 * zt.grad.numpy(), rtol=1e-10, atol=1e-15)
+    assert not out["dlogits"][tr == 1].any()
+    assert out["g"][tr == 0].any()                # advantage 0, but the penalty still pulls towards pi_ref
+
+
+def test_kl_penalty_closed_forms():
+    # the estimator is >= 0, zero with zero slope where pi = pi_ref, and the penalty alone gives
+    # g = grad_scale beta w (1 - pi_ref / pi)
+    V, T = 5, 4
+    rng = np.random.default_rng(9)
+    z = rng.normal(size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    tr = np.zeros(T, np.int32)
+    lp = np.array([orc.logprob_row(z[t], y[t])[0] for t in range(T)])
+    same = orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(1), np.array([0.5]), 0.2, 0.2, z64=z,
+                             kl_coef=0.1, ref_logprob=lp)
+    assert same["loss"] == 0.0 and not same["g"].any() and not same["dlogits"].any()
+    ref_lp = lp + np.array([0.3, -0.2, 0.05, -1.0])
+    out = orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(1), np.array([0.5]), 0.2, 0.2, grad_scale=3.0,
+                            z64=z, kl_coef=0.1, ref_logprob=ref_lp)
+    d = ref_lp - lp
+    assert (np.exp(d) - d - 1 > 0).all()
+    assert abs(out["loss"] - 0.1 * 0.5 * (np.exp(d) - d - 1).sum()) < 1e-16
+    assert np.allclose(out["g"], 3.0 * 0.1 * 0.5 * (1 - np.exp(d)), rtol=1e-14)
+    h = 1e-6
+    for t in range(T):
+        for j in range(V):
+            zp, zm = z.copy(), z.copy()
+            zp[t, j] += h
+            zm[t, j] -= h
+            f = lambda zz: orc.grpo_loss_bwd(None, "f64", V, y, lp, tr, np.zeros(1), np.array([0.5]), 0.2, 0.2,
+                                             want_dlogits=False, z64=zz, kl_coef=0.1, ref_logprob=ref_lp)["loss"]
+            assert abs((f(zp) - f(zm)) / (2 * h) - out["dlogits"][t, j] / 3.0) < 1e-9
+
+
 def test_clip_edge_counts_as_unclipped():
     for A, lp_minus_old in ((1.0, math.log(1.2)), (-1.0, math.log(0.8))):
         rho = math.exp(lp_minus_old)
