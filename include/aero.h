@@ -134,6 +134,12 @@ aero_status aero_logprob_fwd(
  * entropy_coef = c != 0 every token of a rollout with w != 0, whatever A or the clip decision,
  *     loss -= c * w * H_t,   dlogits[t, j] += grad_scale * c * w * p_j * (ln p_j + H_t),
  *     p_j = exp(z[t,j] - lse[t]), H_t = entropy of row t.
+ * KL penalty (the - beta D_KL(pi || pi_ref) term of Eq. 2; the paper names no estimator, the
+ * per-token one of the GRPO literature is used): with kl_coef = beta != 0 every token of a rollout
+ * with w != 0, clipped or not,
+ *     d = ref_logprob[t] - logprob[t],  loss += beta * w * (exp(d) - d - 1),
+ *     g_t += grad_scale * beta * w * (1 - exp(d)).
+ * With beta != 0 the lse == NULL form of the call takes two passes over HBM.
  *
  * logits / dlogits  [T, ld], same dtype and ld; dlogits may alias logits (in place).
  * lse      f32[T] from aero_logprob_fwd, or NULL: then the statistics are computed here.  With
@@ -144,6 +150,8 @@ aero_status aero_logprob_fwd(
  *          (AERO_ERR_NULL if missing then), may be NULL otherwise.
  * old_logprob f32[T]; token_rollout i32[T] (-1 = padding); adv, weight f32[R].
  * entropy_coef  c above; 0 switches the term off (NaN: AERO_ERR_SHAPE).
+ * kl_coef, ref_logprob  beta above and f32[T] log pi_ref of the sampled tokens; ref_logprob is read
+ *          only when kl_coef != 0 (AERO_ERR_NULL if missing then).
  * Outputs  loss f32[1] (deterministic: fixed-order reduction); clip_frac f32[1] or NULL
  *          (clipped tokens / tokens with A != 0 and w != 0); dlogits or NULL (loss only);
  *          logprob_out f32[T] or NULL: current log-prob of the tokens that carry signal, 0 elsewhere;
@@ -159,6 +167,7 @@ aero_status aero_grpo_loss_bwd(
     const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight, int32_t R,
     float eps_lo, float eps_hi, float grad_scale, float entropy_coef,
+    float kl_coef, const float* ref_logprob /*nullable*/,
     float* loss, float* clip_frac /*nullable*/, float* logprob_out /*nullable*/,
     float* entropy_out /*nullable*/, float* lse_out /*nullable*/,
     void* dlogits /*nullable*/, int32_t* err_flag /*nullable*/,
@@ -174,8 +183,8 @@ aero_status aero_grpo_loss_bwd(
  * Backward part (old_logprob .. dweight; pass old_logprob == NULL for forward only):
  *   loss f32[1]; dhidden bf16 [T, H] = dz @ weight; dweight [V, H] = dz^T @ hidden in
  *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd
- *   (entropy_coef included: the entropy of the forward part is used, also when the
- *   `entropy` output is NULL).
+ *   (entropy_coef and kl_coef / ref_logprob included: the entropy of the forward part is used,
+ *   also when the `entropy` output is NULL).
  * Rows whose target is negative take no part in the contraction (their outputs are 0); a
  * target >= V is treated the same way and raises AERO_DERR_BAD_TARGET in err_flag.
  * workspace: aero_workspace_bytes(AERO_OP_LMHEAD_FUSED, T, V, H, R, 0) bytes of device memory,
@@ -192,6 +201,7 @@ aero_status aero_lmhead_logprob_fused(
     const float* old_logprob /*nullable => forward only*/, const int32_t* token_rollout,
     const float* adv, const float* weight_rollout, int32_t R,
     float eps_lo, float eps_hi, float grad_scale, float entropy_coef,
+    float kl_coef, const float* ref_logprob /*nullable*/,
     float* loss, float* clip_frac /*nullable*/, void* dhidden, void* dweight, int32_t dweight_dtype,
     int32_t* err_flag /*nullable*/,
     void* workspace, size_t workspace_bytes, void* stream);

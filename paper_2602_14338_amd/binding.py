@@ -64,11 +64,11 @@ def _load() -> C.CDLL:
     lib.aero_logprob_fwd.restype = i32
     lib.aero_logprob_fwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p]
     lib.aero_grpo_loss_bwd.restype = i32
-    lib.aero_grpo_loss_bwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p, i32, f32, f32, f32, f32,
+    lib.aero_grpo_loss_bwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p, i32, f32, f32, f32, f32, f32, p,
                                        p, p, p, p, p, p, p, p, sz, p]
     lib.aero_lmhead_logprob_fused.restype = i32
     lib.aero_lmhead_logprob_fused.argtypes = [p, p, i64, i32, i32, p, p, p, p, p, p, p, p, i32, f32, f32, f32, f32,
-                                              p, p, p, p, i32, p, p, sz, p]
+                                              f32, p, p, p, p, p, i32, p, p, sz, p]
     return lib
 
 
@@ -146,7 +146,7 @@ def aero_logprob_fwd(logits, T: int, V: int, ld: int, targets, row_active, logpr
 def aero_grpo_loss_bwd(logits, T: int, V: int, ld: int, targets, lse, old_logprob, token_rollout, adv, weight,
                        R: int, eps_lo: float, eps_hi: float, grad_scale: float, loss, clip_frac, logprob_out,
                        dlogits, workspace, err_flag=None, entropy_out=None, lse_out=None,
-                       entropy_coef: float = 0.0, entropy=None) -> None:
+                       entropy_coef: float = 0.0, entropy=None, kl_coef: float = 0.0, ref_logprob=None) -> None:
     if dlogits is not None and dlogits.dtype != logits.dtype:
         raise AeroError("dlogits must have the dtype of logits")
     st = _lib.aero_grpo_loss_bwd(
@@ -155,6 +155,7 @@ def aero_grpo_loss_bwd(logits, T: int, V: int, ld: int, targets, lse, old_logpro
         _ptr(old_logprob, torch.float32, "old_logprob"),
         _ptr(token_rollout, torch.int32, "token_rollout"), _ptr(adv, torch.float32, "adv"),
         _ptr(weight, torch.float32, "weight"), R, eps_lo, eps_hi, grad_scale, entropy_coef,
+        kl_coef, _ptr(ref_logprob, torch.float32, "ref_logprob"),
         _ptr(loss, torch.float32, "loss"), _ptr(clip_frac, torch.float32, "clip_frac"),
         _ptr(logprob_out, torch.float32, "logprob_out"), _ptr(entropy_out, torch.float32, "entropy_out"),
         _ptr(lse_out, torch.float32, "lse_out"), _ptr(dlogits, None, "dlogits"),
@@ -167,14 +168,16 @@ def aero_lmhead_logprob_fused(hidden, weight, T: int, H: int, V: int, targets, l
                               old_logprob=None, token_rollout=None, adv=None, weight_rollout=None, R: int = 0,
                               eps_lo: float = 0.2, eps_hi: float = 0.2, grad_scale: float = 1.0,
                               loss=None, clip_frac=None, dhidden=None, dweight=None, workspace=None,
-                              err_flag=None, entropy_coef: float = 0.0) -> None:
+                              err_flag=None, entropy_coef: float = 0.0, kl_coef: float = 0.0,
+                              ref_logprob=None) -> None:
     st = _lib.aero_lmhead_logprob_fused(
         _ptr(hidden, torch.bfloat16, "hidden"), _ptr(weight, torch.bfloat16, "weight"), T, H, V,
         _ptr(targets, torch.int32, "targets"), _ptr(logprob, torch.float32, "logprob"),
         _ptr(entropy, torch.float32, "entropy"), _ptr(lse, torch.float32, "lse"),
         _ptr(old_logprob, torch.float32, "old_logprob"), _ptr(token_rollout, torch.int32, "token_rollout"),
         _ptr(adv, torch.float32, "adv"), _ptr(weight_rollout, torch.float32, "weight_rollout"), R,
-        eps_lo, eps_hi, grad_scale, entropy_coef, _ptr(loss, torch.float32, "loss"),
+        eps_lo, eps_hi, grad_scale, entropy_coef, kl_coef, _ptr(ref_logprob, torch.float32, "ref_logprob"),
+        _ptr(loss, torch.float32, "loss"),
         _ptr(clip_frac, torch.float32, "clip_frac"),
         _ptr(dhidden, torch.bfloat16, "dhidden"), _ptr(dweight, None, "dweight"),
         _dtype_code(dweight) if dweight is not None else AERO_F32, _ptr(err_flag, torch.int32, "err_flag"),

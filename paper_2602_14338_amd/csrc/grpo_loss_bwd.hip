@@ -11,6 +11,8 @@
 // and e_t pi_j (ln pi_j + H_t), e_t = grad_scale c w, to its gradient row.  A row is then
 // dz_j = pi_j (a z_j + b) + g 1[j = y]  with a = e_t, b = e_t (H_t - lse_t) - g_t, and the
 // kernels with ENT = true read (a, b) per row; with c == 0 the ENT = false kernels run.
+// KL penalty (Eq. 2's beta term, per-token estimator exp(d) - d - 1 with d = log pi_ref(y) - log pi(y)):
+// a per-token scalar like the surrogate, so it only adds to the loss term and to g_t.
 #include "aero_device.h"
 
 namespace aero {
@@ -77,6 +79,7 @@ __global__ __launch_bounds__(256) void k_token_terms(
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R,
     float eps_lo, float eps_hi, float grad_scale, float ent_coef, const float* __restrict__ entropy,
+    float kl_coef, const float* __restrict__ ref_logprob,
     float* __restrict__ g_out, float* __restrict__ term_out, int32_t* __restrict__ flag_out,
     float* __restrict__ ea_out, float* __restrict__ eb_out,
     float* __restrict__ logprob_out, int32_t* __restrict__ err_flag) {
@@ -90,7 +93,7 @@ __global__ __launch_bounds__(256) void k_token_terms(
     if (err_flag) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
   } else if (i >= 0 && y >= 0) {
     const float A = adv[i], w = weight[i];
-    if (w != 0.f && (A != 0.f || ent_coef != 0.f)) {   // decided before the ratio is touched
+    if (w != 0.f && (A != 0.f || ent_coef != 0.f || kl_coef != 0.f)) {   // decided before the ratio is touched
       if constexpr (LP_GIVEN) {
         lp = logprob_in[t];
       } else {
@@ -108,6 +111,12 @@ __global__ __launch_bounds__(256) void k_token_terms(
         term = -w * s;
         g = unclipped ? -grad_scale * w * A * rho : 0.f;
         flag = unclipped ? 1 : 2;
+      }
+      if (kl_coef != 0.f) {   // Eq. 2's beta term, per-token estimator exp(d) - d - 1, d = log pi_ref - log pi
+        const float d = ref_logprob[t] - lp;
+        const float ed = expf(d);
+        term += kl_coef * w * (ed - d - 1.f);
+        g += grad_scale * kl_coef * w * (1.f - ed);
       }
       if (ent_coef != 0.f) {
         const float H = entropy[t];
@@ -417,14 +426,14 @@ static void dispatch_dlogits_dtype(int32_t dtype, bool vec, const void* logits, 
 aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
                                      const float* lse, const float* entropy, const float* old_logprob,
                                      const int32_t* token_rollout, const float* adv, const float* weight, int R,
-                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float* g,
-                                     float* term, int32_t* flag, float* ea, float* eb, float* loss,
-                                     float* clip_frac, int32_t* err_flag, hipStream_t s) {
+                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float kl_coef,
+                                     const float* ref_logprob, float* g, float* term, int32_t* flag, float* ea,
+                                     float* eb, float* loss, float* clip_frac, int32_t* err_flag, hipStream_t s) {
   const unsigned blocks = unsigned((T + 255) / 256);
   if (T > 0)
     hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
                        targets, lse, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                       grad_scale, ent_coef, entropy, g, term, flag, ea, eb, nullptr, err_flag);
+                       grad_scale, ent_coef, entropy, kl_coef, ref_logprob, g, term, flag, ea, eb, nullptr, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, term, flag, T, loss, clip_frac);
   return launch_status();
 }
@@ -435,11 +444,13 @@ extern "C" aero_status aero_grpo_loss_bwd(
     const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
     const float* lse, const float* entropy, const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale,
-    float entropy_coef, float* loss, float* clip_frac, float* logprob_out, float* entropy_out, float* lse_out,
-    void* dlogits, int32_t* err_flag, void* workspace, size_t workspace_bytes, void* stream) {
+    float entropy_coef, float kl_coef, const float* ref_logprob, float* loss, float* clip_frac, float* logprob_out,
+    float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag, void* workspace, size_t workspace_bytes,
+    void* stream) {
   using namespace aero;
   const bool ent = entropy_coef != 0.f;
-  if (!(entropy_coef == entropy_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
+  if (!(entropy_coef == entropy_coef) || !(kl_coef == kl_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
+  if (kl_coef != 0.f && T > 0 && !ref_logprob) return AERO_ERR_NULL;
   if (lse && ent && !entropy) return AERO_ERR_NULL;             // H_t must come with the given lse
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
   if (dtype != AERO_BF16 && dtype != AERO_F32) return AERO_ERR_DTYPE;
@@ -459,7 +470,8 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (!lse) {
     // statistics are computed here; with entropy_out / lse_out they cover every valid row
     const int stats_all = (entropy_out || lse_out) ? 1 : 0;
-    if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
+    // the KL penalty is not in the single-pass kernels: with it the call takes the two-pass route
+    if (kl_coef == 0.f && single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
                                                 eps_lo, eps_hi, grad_scale, entropy_coef, stats_all, ws.g, ws.loss_term,
                                                 ws.flag,
@@ -470,7 +482,7 @@ extern "C" aero_status aero_grpo_loss_bwd(
       return launch_status();
     }
     hipLaunchKernelGGL(k_signal_mask, dim3(blocks), dim3(256), 0, s, T, V, targets, token_rollout, adv, weight,
-                       R, stats_all, ent ? 1 : 0, ws.signal);
+                       R, stats_all, (ent || kl_coef != 0.f) ? 1 : 0, ws.signal);
     float* lse_dst = lse_out ? lse_out : ws.lse;
     float* ent_dst = entropy_out ? entropy_out : (ent ? ws.ent : nullptr);
     aero_status st = logprob_fwd_launch(logits, dtype, T, V, ld, targets, ws.signal,
@@ -486,13 +498,13 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (dtype == AERO_BF16)
     hipLaunchKernelGGL((k_token_terms<true, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       entropy_coef, entropy, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr, ent ? ws.eb : nullptr,
-                       lp_dst, err_flag);
+                       entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr,
+                       ent ? ws.eb : nullptr, lp_dst, err_flag);
   else
     hipLaunchKernelGGL((k_token_terms<false, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       entropy_coef, entropy, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr, ent ? ws.eb : nullptr,
-                       lp_dst, err_flag);
+                       entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr,
+                       ent ? ws.eb : nullptr, lp_dst, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
   if (dlogits) {
     const size_t elt = dtype == AERO_BF16 ? 2 : 4;

@@ -28,9 +28,9 @@ namespace aero {
 aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, const float* logprob,
                                      const float* lse, const float* entropy, const float* old_logprob,
                                      const int32_t* token_rollout, const float* adv, const float* weight, int R,
-                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float* g,
-                                     float* term, int32_t* flag, float* ea, float* eb, float* loss,
-                                     float* clip_frac, int32_t* err_flag, hipStream_t s);
+                                     float eps_lo, float eps_hi, float grad_scale, float ent_coef, float kl_coef,
+                                     const float* ref_logprob, float* g, float* term, int32_t* flag, float* ea,
+                                     float* eb, float* loss, float* clip_frac, int32_t* err_flag, hipStream_t s);
 
 constexpr size_t kWsAlign = 256;
 inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -688,10 +688,11 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     const void* hidden, const void* weight, int64_t T, int32_t H, int32_t V, const int32_t* targets,
     float* logprob, float* entropy, float* lse, const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight_rollout, int32_t R, float eps_lo, float eps_hi, float grad_scale,
-    float entropy_coef, float* loss, float* clip_frac, void* dhidden, void* dweight, int32_t dweight_dtype,
-    int32_t* err_flag, void* workspace, size_t workspace_bytes, void* stream) {
+    float entropy_coef, float kl_coef, const float* ref_logprob, float* loss, float* clip_frac, void* dhidden,
+    void* dweight, int32_t dweight_dtype, int32_t* err_flag, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace aero;
-  if (!(entropy_coef == entropy_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
+  if (!(entropy_coef == entropy_coef) || !(kl_coef == kl_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
+  if (old_logprob && kl_coef != 0.f && T > 0 && !ref_logprob) return AERO_ERR_NULL;
   if (T < 0 || T > 0x7fffff00LL || V < 1 || V > (1 << 24) || H < 8 || H % 8 != 0 || H > (1 << 20) || R < 0)
     return AERO_ERR_SHAPE;
   const bool bwd = old_logprob != nullptr;
@@ -758,8 +759,8 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   float* ea = ent ? reinterpret_cast<float*>(ws + p.off_ea) : nullptr;
   float* eb = ent ? reinterpret_cast<float*>(ws + p.off_eb) : nullptr;
   aero_status st = token_terms_from_logprob(T, V, targets, logprob, lse, ent_arr, old_logprob, token_rollout, adv,
-                                            weight_rollout, R, eps_lo, eps_hi, grad_scale, entropy_coef, g, term, flag,
-                                            ea, eb, loss, clip_frac, err_flag, s);
+                                            weight_rollout, R, eps_lo, eps_hi, grad_scale, entropy_coef, kl_coef,
+                                            ref_logprob, g, term, flag, ea, eb, loss, clip_frac, err_flag, s);
   if (st != AERO_OK) return st;
 
   // ---- compaction and operand copies ----

@@ -64,7 +64,8 @@ def run_fwd(logits_d, T, V, ld, targets, row_active=None, want_entropy=True):
 
 
 def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv, weight, eps=0.2,
-                 grad_scale=1.0, inplace=False, want_dlogits=True, stats=False, entropy_coef=0.0, entropy=None):
+                 grad_scale=1.0, inplace=False, want_dlogits=True, stats=False, entropy_coef=0.0, entropy=None,
+                 kl_coef=0.0, ref_logprob=None):
     R = len(adv)
     ws_bytes = aero.aero_workspace_bytes(binding.OP_GRPO_LOSS_BWD, T=T, V=V, R=R)
     ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=DEV)
@@ -84,7 +85,9 @@ def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv,
                             dev(token_rollout), dev(adv.astype(np.float32)), dev(weight.astype(np.float32)), R,
                             eps, eps, grad_scale, loss, clip, lp_out, dl, ws, err, entropy_out=ent_out,
                             lse_out=lse_out, entropy_coef=entropy_coef,
-                            entropy=dev(entropy.astype(np.float32)) if entropy is not None else None)
+                            entropy=dev(entropy.astype(np.float32)) if entropy is not None else None,
+                            kl_coef=kl_coef,
+                            ref_logprob=dev(ref_logprob.astype(np.float32)) if ref_logprob is not None else None)
     torch.cuda.synchronize()
     return dict(loss=loss, clip_frac=clip, logprob=lp_out, dlogits=dl, err=int(err.item()), entropy=ent_out,
                 lse=lse_out)

@@ -46,7 +46,8 @@ def run_fused(gh, wl, h_bits, w_bits, targets, bwd=None, dweight_dtype=torch.flo
             hd, wd, T, H, V, gh.dev(targets), lp, ent, lse, gh.dev(bwd["old"].astype(np.float32)),
             gh.dev(wl.token_rollout), gh.dev(bwd["adv"].astype(np.float32)), gh.dev(bwd["weight"].astype(np.float32)),
             wl.R, 0.2, 0.2, bwd.get("grad_scale", 1.0), loss, clip, dh, dw, ws, err,
-            entropy_coef=bwd.get("entropy_coef", 0.0))
+            entropy_coef=bwd.get("entropy_coef", 0.0), kl_coef=bwd.get("kl_coef", 0.0),
+            ref_logprob=gh.dev(bwd["ref_lp"].astype(np.float32)) if bwd.get("ref_lp") is not None else None)
         out.update(loss=loss, clip_frac=clip, dhidden=dh, dweight=dw)
     torch.cuda.synchronize()
     out["err"] = int(err.item())
@@ -85,15 +86,19 @@ def test_fused_forward(gh, T, H, V):
         assert not got[tg < 0].any()
 
 
-def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, grad_scale=1.0, entropy_coef=0.0):
+def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, grad_scale=1.0, entropy_coef=0.0,
+              kl_coef=0.0):
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     fwd = orc.lmhead_fused(h, W, wl.targets)
     old = ai.draw_old_logprob(fwd["logprob"], wl.seed, sigma=sigma_old)
     a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+    ref_lp = (old + np.random.default_rng(wl.seed + 77).normal(0, 0.2, size=old.shape)).astype(np.float32) \
+        if kl_coef != 0.0 else None
     ref = orc.lmhead_fused(h, W, wl.targets, old, wl.token_rollout, a32, w32, np.float32(0.2), np.float32(0.2),
-                           grad_scale, entropy_coef=entropy_coef)
+                           grad_scale, entropy_coef=entropy_coef, kl_coef=kl_coef, ref_logprob=ref_lp)
     out = run_fused(gh, wl, h, W, wl.targets,
-                    bwd=dict(old=old, adv=a32, weight=w32, grad_scale=grad_scale, entropy_coef=entropy_coef),
+                    bwd=dict(old=old, adv=a32, weight=w32, grad_scale=grad_scale, entropy_coef=entropy_coef,
+                             kl_coef=kl_coef, ref_lp=ref_lp),
                     dweight_dtype=dweight_dtype)
     assert out["err"] == 0
     assert abs(out["loss"].item() - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"])
@@ -135,6 +140,15 @@ def test_fused_entropy_bonus(gh):
               grad_scale=8.0)
     wl, h, W = make(2816, 128, 40000, Q=8, len_hi=500)     # several vocabulary chunks
     check_bwd(gh, wl, h, W, dict(), sigma_old=0.05, entropy_coef=1e-3)
+
+
+def test_fused_kl_penalty(gh):
+    wl, h, W = make(520, 128, 1000, sigma_w=0.3)
+    ref0, _ = check_bwd(gh, wl, h, W, dict())
+    ref, _ = check_bwd(gh, wl, h, W, dict(), kl_coef=0.04)
+    assert ref["loss"] > ref0["loss"] and (ref["g"] != 0).sum() > (ref0["g"] != 0).sum()
+    check_bwd(gh, wl, h, W, dict(reject_enable=1, posterior_mode=1), kl_coef=0.04, entropy_coef=1e-3,
+              dweight_dtype=torch.bfloat16, grad_scale=8.0)
 
 
 def test_fused_all_groups_zero_variance(gh):

@@ -195,21 +195,26 @@ def elt_rounding(dtype, ref_abs):
 
 
 def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
-                   expect_clip=False, stats=False, entropy_coef=0.0):
+                   expect_clip=False, stats=False, entropy_coef=0.0, kl_coef=0.0):
     host = wl.logits_rows(0, wl.T)
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     active = (wl.token_rollout >= 0).astype(np.uint8)
     lp_ref, ent_ref, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets, active)
     old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=sigma_old)
     eps = np.float32(wl.eps)
+    # log-probs of a reference policy: the behaviour ones moved by seeded noise (input data only)
+    ref_lp = (old + np.random.default_rng(wl.seed + 77).normal(0, 0.2, size=old.shape)).astype(np.float32) \
+        if kl_coef != 0.0 else None
     ref = orc.grpo_loss_bwd(host, wl.dtype, wl.V, wl.targets, old, wl.token_rollout, ga["adv"].astype(np.float32),
-                            ga["weight"].astype(np.float32), eps, eps, grad_scale, entropy_coef=entropy_coef)
+                            ga["weight"].astype(np.float32), eps, eps, grad_scale, entropy_coef=entropy_coef,
+                            kl_coef=kl_coef, ref_logprob=ref_lp)
     d = gh.logits_to_dev(host, wl.dtype)
     lse_d = gh.dev(lse_ref.astype(np.float32)) if use_oracle_lse else None
     out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, wl.token_rollout,
                           ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace, stats=stats,
                           entropy_coef=entropy_coef,
-                          entropy=ent_ref if (use_oracle_lse and entropy_coef != 0.0) else None)
+                          entropy=ent_ref if (use_oracle_lse and entropy_coef != 0.0) else None,
+                          kl_coef=kl_coef, ref_logprob=ref_lp)
     assert out["err"] == 0
     loss = out["loss"].item()
     assert abs(loss - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"]), (loss, ref["loss"])
@@ -272,6 +277,27 @@ def test_entropy_bonus_cfg2_reduced(gh, V, ld, slots):
     wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
     check_loss_bwd(gh, wl, dict(), entropy_coef=1e-3)
     check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, expect_clip=True, entropy_coef=0.02, stats=True)
+
+
+@pytest.mark.parametrize("cfg,kw", [("cfg1", dict()), ("cfg2", dict(V=151936, ld=151936, slots=6, len_lo=1, len_hi=6)),
+                                    ("cfg2", dict(V=4999, ld=4999, slots=10, len_lo=1, len_hi=10))])
+def test_kl_penalty(gh, cfg, kw):
+    """Eq. 2's beta term: every token of a weighted rollout is pulled towards the reference policy,
+    also in the all-equal groups and on clipped tokens; alone and together with the entropy bonus."""
+    wl = ai.make_config(cfg, **kw)
+    ref0, _ = check_loss_bwd(gh, wl, dict(), sigma_old=0.3)
+    ref, _ = check_loss_bwd(gh, wl, dict(), sigma_old=0.3, kl_coef=0.04, expect_clip=True)
+    assert ref["loss"] > ref0["loss"] and (ref["g"] != 0).sum() > (ref0["g"] != 0).sum()
+    check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=False, kl_coef=0.04,
+                   entropy_coef=1e-3, grad_scale=4.0, stats=True)
+
+
+def test_kl_penalty_needs_the_reference_logprobs(gh):
+    wl = ai.make_config("cfg1")
+    d = gh.logits_to_dev(wl.logits_rows(0, wl.T), wl.dtype)
+    with pytest.raises(Exception):
+        gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, None, np.zeros(wl.T), wl.token_rollout,
+                        np.zeros(wl.R), np.zeros(wl.R), kl_coef=0.1)
 
 
 def test_entropy_bonus_needs_the_entropy_array(gh):
