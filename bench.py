@@ -103,7 +103,7 @@ def machine_ceilings(torch):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+        print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 

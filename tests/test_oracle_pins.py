@@ -178,7 +178,7 @@ def test_keep_set_matches_rank_counting_brute_force():
 
 def test_posterior_mode():
     """Strategy 2: u~ = (c + 1)/(n + 2) stays inside (0, 1); 4 rollouts are kept.  The
-    divisor sqrt(u~(1-u~)) is this build's reading, so the +-1/3 below pins the reading's
+    divisor sqrt(u~(1-u~)) is a reading taken here, so the +-1/3 below pins the reading's
     closed form only."""
     n = int(PV["n_explore"])
     a0, b0 = PV["prior_alpha0"], PV["prior_beta0"]
