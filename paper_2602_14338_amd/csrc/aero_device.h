@@ -88,11 +88,18 @@ __device__ __forceinline__ void stat_update(RowStat& st, const float (&z)[N]) {
   } else if constexpr (N == 2) {
     vm = fmaxf(vm, z[1]);
   }
-  if (vm > st.m + kLazy) {   // also taken on first use (m = -inf)
-    float f = (st.m == -INFINITY) ? 0.f : exp2_fast((st.m - vm) * kLog2e);
-    st.s *= f;
-    st.sz *= f;
-    st.m = vm;
+  // also taken on first use (m = -inf).  The wave-uniform test in front keeps the compiler from
+  // turning the rare rescale into always-executed predicated code (about two extra vector
+  // instructions per logit in kernels whose vector ALUs are close to saturated).
+  const bool grow = vm > st.m + kLazy;
+  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    asm volatile("" ::: "memory");   // a side effect: the block cannot be if-converted
+    if (grow) {
+      float f = (st.m == -INFINITY) ? 0.f : exp2_fast((st.m - vm) * kLog2e);
+      st.s *= f;
+      st.sz *= f;
+      st.m = vm;
+    }
   }
   const float c = -st.m * kLog2e;
 #pragma unroll
