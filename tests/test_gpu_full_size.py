@@ -112,6 +112,24 @@ def logits_full_size(gh, name, params):
     # every row without signal is exactly +0 in the whole tensor
     nz_rows = (out["dlogits"].view(torch.int16) != 0).any(dim=1).cpu().numpy()
     assert not nz_rows[~signal].any() and nz_rows[g_ref != 0].all()
+
+    # the same step as the one-call route the bench times: statistics, loss and gradient in one
+    # pass, log-prob / entropy / lse written for every valid row
+    del out
+    torch.cuda.empty_cache()
+    one = gh.run_loss_bwd(logits, T, V, ld, wl.targets, None, old, tr, ga["adv"], ga["weight"], eps=float(eps),
+                          stats=True)
+    assert one["err"] == 0
+    assert abs(one["loss"].item() - loss_ref) <= gh.loss_bound(loss_ref, terms)
+    assert abs(one["clip_frac"].item() - (n_clip / n_sig if n_sig else 0.0)) < 1e-6
+    valid = active.astype(bool)
+    for key, want_all in (("logprob", lp_ref), ("entropy", ent_ref), ("lse", lse_ref)):
+        got = one[key].cpu().numpy().astype(np.float64)
+        assert np.abs(got[valid] - want_all[valid]).max() <= 2e-3 and not got[~valid].any(), key
+    dz1 = one["dlogits"][torch.from_numpy(sel).to(gh.DEV)].float().cpu().numpy().astype(np.float64)[:, :V]
+    assert (np.abs(dz1 - want) <= 1e-2 * np.abs(sub["g"])[:, None] + np.abs(want) * 2.0 ** -8 + 1e-30).all()
+    nz_rows = (one["dlogits"].view(torch.int16) != 0).any(dim=1).cpu().numpy()
+    assert not nz_rows[~signal].any() and nz_rows[g_ref != 0].all()
     return wl
 
 
