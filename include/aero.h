@@ -139,7 +139,6 @@ aero_status aero_logprob_fwd(
  * with w != 0, clipped or not,
  *     d = ref_logprob[t] - logprob[t],  loss += beta * w * (exp(d) - d - 1),
  *     g_t += grad_scale * beta * w * (1 - exp(d)).
- * With beta != 0 the lse == NULL form of the call takes two passes over HBM.
  *
  * logits / dlogits  [T, ld], same dtype and ld; dlogits may alias logits (in place).
  * lse      f32[T] from aero_logprob_fwd, or NULL: then the statistics are computed here.  With

@@ -24,9 +24,10 @@ bool single_pass_applicable(int32_t dtype, int V, int64_t ld, const void* logits
 aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
                                const float* old_logprob, const int32_t* token_rollout, const float* adv,
                                const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
-                               float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
-                               float* logprob_out, float* entropy_out, float* lse_out, void* dlogits,
-                               int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s);
+                               float ent_coef, float kl_coef, const float* ref_logprob, int stats_all, float* g,
+                               float* term, int32_t* flag, float* logprob_out, float* entropy_out, float* lse_out,
+                               void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
+                               hipStream_t s);
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
@@ -470,10 +471,10 @@ extern "C" aero_status aero_grpo_loss_bwd(
   if (!lse) {
     // statistics are computed here; with entropy_out / lse_out they cover every valid row
     const int stats_all = (entropy_out || lse_out) ? 1 : 0;
-    // the KL penalty is not in the single-pass kernels: with it the call takes the two-pass route
-    if (kl_coef == 0.f && single_pass_applicable(dtype, V, ld, logits, dlogits)) {
+    if (single_pass_applicable(dtype, V, ld, logits, dlogits)) {
       const aero_status sp = single_pass_launch(logits, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R,
-                                                eps_lo, eps_hi, grad_scale, entropy_coef, stats_all, ws.g, ws.loss_term,
+                                                eps_lo, eps_hi, grad_scale, entropy_coef, kl_coef, ref_logprob, stats_all, ws.g,
+                                                ws.loss_term,
                                                 ws.flag,
                                                 logprob_out, entropy_out, lse_out, dlogits, err_flag, ws.counter,
                                                 reinterpret_cast<int32_t*>(ws.lp_tmp), s);

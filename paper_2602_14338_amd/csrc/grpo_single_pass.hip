@@ -16,13 +16,15 @@ constexpr int kSpNT = 1024;
 // (filled directly by buffer_load ... lds, each lane reads back only what its own wave loaded),
 // because 20 x 4 data registers plus the working set exceed the 128 VGPRs a 1024-thread
 // workgroup may use and the overflow would otherwise go to scratch memory in HBM.
-// ENT: the entropy-bonus term is part of the loss and of the gradient row.
+// ENT: the optional terms are on: the entropy bonus (loss and gradient row) and / or the KL penalty
+// (a per-token scalar added to the loss term and to g); either coefficient may be 0.
 template <int NV, int NL, bool ENT>
 __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
-    float grad_scale, float ent_coef, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
+    float grad_scale, float ent_coef, float kl_coef, const float* __restrict__ ref_logprob, int stats_all,
+    float* __restrict__ g_out, float* __restrict__ term_out,
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag) {
   __shared__ RowStat lds[kSpNT / kWave];
@@ -138,6 +140,12 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
   }
   const float ent = lse - st.sz / st.s;
   // gradient row: dz_j = pi_j (a z_j + b) + g 1[j = y]; without the entropy bonus a = 0, b = -g
+  if (bonus && kl_coef != 0.f) {   // Eq. 2's beta term: exp(d) - d - 1, d = log pi_ref - log pi
+    const float d = ref_logprob[t] - lp;
+    const float ed = expf(d);
+    term += kl_coef * w * (ed - d - 1.f);
+    g += grad_scale * kl_coef * w * (1.f - ed);
+  }
   float a = 0.f, ng = -g;
   if (bonus) {
     term -= ent_coef * w * ent;
@@ -269,7 +277,8 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     const uint16_t* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ old_logprob, const int32_t* __restrict__ token_rollout,
     const float* __restrict__ adv, const float* __restrict__ weight, int R, float eps_lo, float eps_hi,
-    float grad_scale, float ent_coef, int stats_all, float* __restrict__ g_out, float* __restrict__ term_out,
+    float grad_scale, float ent_coef, float kl_coef, const float* __restrict__ ref_logprob, int stats_all,
+    float* __restrict__ g_out, float* __restrict__ term_out,
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter,
     const int32_t* __restrict__ order) {
@@ -375,6 +384,12 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
       }
       if constexpr (ENT) {
         if (cur.bonus) {
+          if (kl_coef != 0.f) {   // Eq. 2's beta term: exp(d) - d - 1, d = log pi_ref - log pi
+            const float d = ref_logprob[t] - lp;
+            const float ed = expf(d);
+            term += kl_coef * cur.w * (ed - d - 1.f);
+            g += grad_scale * kl_coef * cur.w * (1.f - ed);
+          }
           term -= ent_coef * cur.w * ent;
           ea = grad_scale * ent_coef * cur.w;
         }
@@ -483,13 +498,14 @@ template <bool ENT>
 static aero_status single_pass_launch_t(const uint16_t* z, int64_t T, int V, int64_t ld, const int32_t* targets,
                                         const float* old_logprob, const int32_t* token_rollout, const float* adv,
                                         const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
-                                        float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
+                                        float ent_coef, float kl_coef, const float* ref_logprob, int stats_all,
+                                        float* g, float* term, int32_t* flag,
                                         float* logprob_out, float* entropy_out, float* lse_out, uint16_t* dz,
                                         int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s) {
   if (V / 8 <= 8 * kSpNT) {
     hipLaunchKernelGGL((k_row_single_pass<8, 0, ENT>), dim3(unsigned(T)), dim3(kSpNT), 0, s, z, T, V, ld, targets,
-                       old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, stats_all, g,
-                       term, flag, logprob_out, entropy_out, lse_out, dz, err_flag);
+                       old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, kl_coef, ref_logprob,
+                       stats_all, g, term, flag, logprob_out, entropy_out, lse_out, dz, err_flag);
     return AERO_OK;
   }
   constexpr int NL = 9;
@@ -512,27 +528,28 @@ static aero_status single_pass_launch_t(const uint16_t* z, int64_t T, int V, int
   hipLaunchKernelGGL(k_row_order, dim3(unsigned((T + 255) / 256)), dim3(256), 0, s, T, V, R, targets, token_rollout,
                      adv, weight, stats_all, ENT ? 1 : 0, row_counter, row_order);
   hipLaunchKernelGGL((k_row_stream<20, NL, ENT>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets,
-                     old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, stats_all, g,
-                     term, flag, logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);
+                     old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, kl_coef, ref_logprob,
+                     stats_all, g, term, flag, logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);
   return AERO_OK;
 }
 
-// ent_coef != 0 selects the kernels that carry the entropy-bonus term.
+// A non-zero entropy or KL coefficient selects the kernels that carry the optional terms.
 aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
                                const float* old_logprob, const int32_t* token_rollout, const float* adv,
                                const float* weight, int R, float eps_lo, float eps_hi, float grad_scale,
-                               float ent_coef, int stats_all, float* g, float* term, int32_t* flag,
-                               float* logprob_out, float* entropy_out, float* lse_out, void* dlogits,
-                               int32_t* err_flag, int32_t* row_counter, int32_t* row_order, hipStream_t s) {
+                               float ent_coef, float kl_coef, const float* ref_logprob, int stats_all, float* g,
+                               float* term, int32_t* flag, float* logprob_out, float* entropy_out, float* lse_out,
+                               void* dlogits, int32_t* err_flag, int32_t* row_counter, int32_t* row_order,
+                               hipStream_t s) {
   const uint16_t* z = reinterpret_cast<const uint16_t*>(logits);
   uint16_t* dz = reinterpret_cast<uint16_t*>(dlogits);
-  if (ent_coef != 0.f)
+  if (ent_coef != 0.f || kl_coef != 0.f)
     return single_pass_launch_t<true>(z, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                                      grad_scale, ent_coef, stats_all, g, term, flag, logprob_out, entropy_out,
-                                      lse_out, dz, err_flag, row_counter, row_order, s);
+                                      grad_scale, ent_coef, kl_coef, ref_logprob, stats_all, g, term, flag, logprob_out,
+                                      entropy_out, lse_out, dz, err_flag, row_counter, row_order, s);
   return single_pass_launch_t<false>(z, T, V, ld, targets, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
-                                     grad_scale, 0.f, stats_all, g, term, flag, logprob_out, entropy_out, lse_out, dz,
-                                     err_flag, row_counter, row_order, s);
+                                     grad_scale, 0.f, 0.f, nullptr, stats_all, g, term, flag, logprob_out, entropy_out,
+                                     lse_out, dz, err_flag, row_counter, row_order, s);
 }
 
 }  // namespace aero

@@ -280,6 +280,7 @@ def test_entropy_bonus_cfg2_reduced(gh, V, ld, slots):
 
 
 @pytest.mark.parametrize("cfg,kw", [("cfg1", dict()), ("cfg2", dict(V=151936, ld=151936, slots=6, len_lo=1, len_hi=6)),
+                                    ("cfg2", dict(V=32768, ld=32768, slots=8, len_lo=1, len_hi=8)),
                                     ("cfg2", dict(V=4999, ld=4999, slots=10, len_lo=1, len_hi=10))])
 def test_kl_penalty(gh, cfg, kw):
     """Eq. 2's beta term: every token of a weighted rollout is pulled towards the reference policy,
@@ -288,6 +289,7 @@ def test_kl_penalty(gh, cfg, kw):
     ref0, _ = check_loss_bwd(gh, wl, dict(), sigma_old=0.3)
     ref, _ = check_loss_bwd(gh, wl, dict(), sigma_old=0.3, kl_coef=0.04, expect_clip=True)
     assert ref["loss"] > ref0["loss"] and (ref["g"] != 0).sum() > (ref0["g"] != 0).sum()
+    check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, kl_coef=0.04)   # one-call route, penalty alone
     check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=False, kl_coef=0.04,
                    entropy_coef=1e-3, grad_scale=4.0, stats=True)
 
