@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
 # WRITE_SIZE, each scaled by what the same counter reads for an elementwise copy of known size;
 # see profiles/logits_path_cfg2_hbm_traffic.txt).  Valid only for the kernel sources it was
 # measured on: the figure is reported only while their hash still matches.
-MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8592e+09, "sources_sha256": "fe634c2aa514135d37a042bf3d1d579761fc33f5194ad034b9208d61dbb659db"}}
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8595e+09, "sources_sha256": "c0ac81581d75430026bec98f21e8babfafb9d5822646f5689dfd4b07e6d03609"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
 
 
