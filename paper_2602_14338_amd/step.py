@@ -74,10 +74,12 @@ def loss_bwd_microbatches(token_rollout: torch.Tensor, logits_of: Callable[[int]
                           dlogits_of: Callable[[int], Optional[torch.Tensor]], adv: torch.Tensor,
                           weight: torch.Tensor, V: int, ld: int, eps_lo: float, eps_hi: float,
                           grad_scale: float = 1.0, entropy_coef: float = 0.0,
-                          err_flag: Optional[torch.Tensor] = None) -> torch.Tensor:
+                          err_flag: Optional[torch.Tensor] = None, kl_coef: float = 0.0,
+                          ref_logprob_of: Optional[Callable[[int], torch.Tensor]] = None) -> torch.Tensor:
     """Runs the loss / gradient call on every micro-batch of ``token_rollout`` ([n_mb, mb_tokens],
     device int32) and returns the per-micro-batch losses (device f32 [n_mb]); their sum is the
-    step's loss.  ``*_of(k)`` hand over the tensors of micro-batch k."""
+    step's loss.  ``*_of(k)`` hand over the tensors of micro-batch k; ``ref_logprob_of`` is needed
+    only with a non-zero ``kl_coef`` (Eq. 2's beta)."""
     n_mb, mb_tokens = token_rollout.shape
     dev = token_rollout.device
     R = adv.numel()
@@ -87,5 +89,7 @@ def loss_bwd_microbatches(token_rollout: torch.Tensor, logits_of: Callable[[int]
     for k in range(n_mb):
         binding.aero_grpo_loss_bwd(logits_of(k), mb_tokens, V, ld, targets_of(k), None, old_logprob_of(k),
                                    token_rollout[k], adv, weight, R, eps_lo, eps_hi, grad_scale, losses[k:k + 1],
-                                   None, None, dlogits_of(k), ws, err_flag, entropy_coef=entropy_coef)
+                                   None, None, dlogits_of(k), ws, err_flag, entropy_coef=entropy_coef,
+                                   kl_coef=kl_coef,
+                                   ref_logprob=ref_logprob_of(k) if ref_logprob_of is not None else None)
     return losses[:n_mb]

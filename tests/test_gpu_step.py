@@ -18,13 +18,15 @@ def gh():
     return gpu_helpers
 
 
-@pytest.mark.parametrize("mode", ["grpo", "aero"])
+@pytest.mark.parametrize("mode", ["grpo", "aero", "aero+terms"])
 def test_step_matches_checker(gh, mode):
     import paper_2602_14338_amd as aero
     from paper_2602_14338_amd import step
     V, mb_tokens = 512, 96
     groups = ai.make_step_groups(seed=11, Q=10, N=8, len_lo=3, len_hi=40, zero_var_frac=0.35)
-    params = dict(reject_enable=1, posterior_mode=1) if mode == "aero" else dict()
+    params = dict(reject_enable=1, posterior_mode=1) if mode != "grpo" else dict()
+    # "+terms": the entropy bonus (Table 8) and Eq. 2's KL penalty ride along on every micro-batch
+    ent_coef, kl_coef = (0.01, 0.05) if mode == "aero+terms" else (0.0, 0.0)
     ga = orc.group_advantage(groups.rewards, groups.lengths, groups.group_offsets, groups.keep_priority,
                              OracleParams(**params))
     cur = step.curate(gh.dev(groups.rewards), gh.dev(groups.lengths), gh.dev(groups.group_offsets),
@@ -32,7 +34,7 @@ def test_step_matches_checker(gh, mode):
     torch.cuda.synchronize()
     keep = cur.keep_mask.cpu().numpy()
     assert np.array_equal(keep, ga["keep_mask"]) and int(cur.err.item()) == 0
-    if mode == "aero":
+    if mode != "grpo":
         assert keep.sum() < groups.R          # something was dropped and is never packed
     rollouts = np.nonzero(keep)[0]
     plan = step.plan_microbatches(groups.lengths, rollouts, mb_tokens)
@@ -42,26 +44,33 @@ def test_step_matches_checker(gh, mode):
     z = ai.normal_rows(groups.seed, 7, 0, T, V, 2.0, "f32")
     tr = plan.reshape(-1)
     targets = np.where(tr >= 0, np.random.default_rng(3).integers(0, V, size=T), -1).astype(np.int32)
-    lp_ref, _, _ = orc.logprob_fwd(z, "f32", V, targets, (tr >= 0).astype(np.uint8))
+    lp_ref, ent_ref, _ = orc.logprob_fwd(z, "f32", V, targets, (tr >= 0).astype(np.uint8))
     old = ai.draw_old_logprob(lp_ref, groups.seed, sigma=0.3)
     a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
-    ref = orc.grpo_loss_bwd(z, "f32", V, targets, old, tr, a32, w32, np.float32(0.2), np.float32(0.2), 1.0)
+    ref_lp = ai.draw_old_logprob(lp_ref, groups.seed + 1, sigma=0.2) if kl_coef else None
+    ref = orc.grpo_loss_bwd(z, "f32", V, targets, old, tr, a32, w32, np.float32(0.2), np.float32(0.2), 1.0,
+                            entropy_coef=ent_coef, kl_coef=kl_coef, ref_logprob=ref_lp)
 
     zd = gh.dev(z).view(n_mb, mb_tokens, V)
     td = gh.dev(targets).view(n_mb, mb_tokens)
     od = gh.dev(old.astype(np.float32)).view(n_mb, mb_tokens)
     dz = torch.full_like(zd, 7.0)
     err = torch.zeros(1, dtype=torch.int32, device=gh.DEV)
+    rd = gh.dev(ref_lp.astype(np.float32)).view(n_mb, mb_tokens) if kl_coef else None
     losses = step.loss_bwd_microbatches(gh.dev(plan), lambda k: zd[k], lambda k: td[k], lambda k: od[k],
-                                        lambda k: dz[k], cur.adv, cur.weight, V, V, 0.2, 0.2, err_flag=err)
+                                        lambda k: dz[k], cur.adv, cur.weight, V, V, 0.2, 0.2, err_flag=err,
+                                        entropy_coef=ent_coef, kl_coef=kl_coef,
+                                        ref_logprob_of=(lambda k: rd[k]) if kl_coef else None)
     torch.cuda.synchronize()
     assert int(err.item()) == 0 and losses.shape == (n_mb,)
     total = losses.double().sum().item()
     assert abs(total - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"])
     got = dz.view(T, V).cpu().numpy().astype(np.float64)
-    bound = 1e-2 * np.abs(ref["g"])[:, None] + np.abs(ref["dlogits"]) * 2.0 ** -23 + 1e-30
+    # scale of a row: |g_t| for the surrogate and the KL term, |e_t| (1 + H_t) for the entropy term
+    scale = np.abs(ref["g"]) + np.abs(ref["e"]) * (1.0 + ent_ref)
+    bound = 1e-2 * scale[:, None] + np.abs(ref["dlogits"]) * 2.0 ** -23 + 1e-30
     assert (np.abs(got - ref["dlogits"]) <= bound).all()
-    assert not got[ref["g"] == 0].any()
+    assert not got[(ref["g"] == 0) & (ref["e"] == 0)].any()
 
 
 @pytest.mark.parametrize("S", [0, 2])
