@@ -97,6 +97,23 @@ def machine_ceilings(torch):
     w7 = (torch.randn((V, 3584), device=dev, generator=gen) * 0.02).to(torch.bfloat16)
     ms = timed(lambda: torch.matmul(h7, w7.t()), reps=3)
     out["matmul_bf16_T16384_V151936_H3584_TFLOPs"] = 2.0 * T * V * 3584 / ms / 1e9
+    del h7, w7
+    # The same contractions on all-zero operands: identical instruction stream and memory traffic, but no
+    # bit toggles in the matrix pipes and on the data paths.  The gap to the Gaussian-operand figures is what
+    # the power limit of this part costs (the clock it settles at under each load is in the counters).
+    hz, wz = torch.zeros_like(h), torch.zeros_like(w)
+    ms = timed(lambda: torch.matmul(hz, wz.t()), reps=5)
+    out["matmul_bf16_T16384_V151936_H1536_zero_operands_TFLOPs"] = 2.0 * T * V * H / ms / 1e9
+    import paper_2602_14338_amd as aero
+    from paper_2602_14338_amd import binding
+    targets = torch.zeros(T, dtype=torch.int32, device=dev)
+    lp, ent, lse = (torch.empty(T, device=dev) for _ in range(3))
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = torch.empty(aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=T, V=V, H=H, R=1), dtype=torch.uint8, device=dev)
+    for tag, hh, ww in (("gaussian", h, w), ("zero", hz, wz)):
+        ms = timed(lambda: aero.aero_lmhead_logprob_fused(hh, ww, T, H, V, targets, lp, ent, lse, workspace=ws,
+                                                          err_flag=err), reps=5)
+        out["fused_forward_call_T16384_V151936_H1536_%s_operands_TFLOPs" % tag] = 2.0 * T * V * H / ms / 1e9
     print(json.dumps(out))
 
 
