@@ -6,7 +6,8 @@
 //
 // Two main loops share the accumulator layout:
 //   gemm_tile_dma  operands go HBM -> LDS directly (buffer_load ... lds), two stages of
-//                  256 x 64 slices; needs K % 64 == 0 and 16-byte aligned rows
+//                  256 x 64 slices, L2 warmed two slices ahead; needs K % 64 == 0 and
+//                  16-byte aligned rows
 //   gemm_tile      register-staged 256 x 64 slices with explicit predication; any K % 8 == 0
 #pragma once
 #include "aero_device.h"
@@ -19,7 +20,9 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int kTile = 256;          // tile edge in both output dimensions
 constexpr int kGemmNT = 512;        // threads per workgroup (8 waves)
 constexpr int kMB = 4, kNB = 2;     // 32 x 32 blocks per wave: 128 rows x 64 columns
-constexpr size_t kGemmLdsBytes = 131072;   // two stages of (256 + 256) x 64 bf16
+constexpr size_t kGemmStageBytes = 131072;  // two stages of (256 + 256) x 64 bf16
+constexpr size_t kWarmSinkOff = 135168;     // past the largest epilogue staging area (256 x 264 bf16)
+constexpr size_t kGemmLdsBytes = kWarmSinkOff + 2048;   // + a 256-byte sink per wave for the warm-up loads
 
 // Position of an accumulator element inside the 256 x 256 tile.
 //   block (mb, nb) of wave (wm in 0..1, wn in 0..3); register i of lane l:
@@ -88,7 +91,7 @@ __device__ __forceinline__ void frags_mma(const Frags& f, Acc& acc) {
 // ------------------------------------------------------------------------------------------
 constexpr int kBK = 64;
 constexpr int kSliceElems = kTile * kBK;
-static_assert(size_t(4) * kSliceElems * 2 <= kGemmLdsBytes, "double buffer must fit the LDS budget");
+static_assert(size_t(4) * kSliceElems * 2 <= kGemmStageBytes, "double buffer must fit the LDS budget");
 constexpr int kVecPerThread = kTile * (kBK / 8) / kGemmNT;   // 4
 
 __device__ __forceinline__ void slice_load(const uint16_t* __restrict__ base, int64_t ld, int row0,
@@ -183,7 +186,7 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, int64_
 // ------------------------------------------------------------------------------------------
 constexpr int kDK = kBK;                         // K slice of the fast loop
 constexpr int kDStageElems = 2 * kTile * kDK;    // A then B
-static_assert(size_t(2) * kDStageElems * 2 <= kGemmLdsBytes, "two stages must fit the LDS budget");
+static_assert(size_t(2) * kDStageElems * 2 <= kGemmStageBytes, "two stages must fit the LDS budget");
 
 // An operand of the fast loop: rows of 64-wide K slices.  Element (row, k) lives at
 //   base + (k / 64) * kstep + row * ld + k % 64
@@ -248,6 +251,9 @@ __device__ __forceinline__ void frags_load(Frags& f, const uint16_t* stage, int 
     f.b[nb] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_off(wn * 64 + nb * 32 + (lane & 31), chunk));
 }
 
+// WARM: L2 warm-up two slices ahead (see below); a few per cent on the contractions whose
+// operands come from large read-only arrays, a loss on the split-K dhidden contraction.
+template <bool WARM>
 __device__ __forceinline__ void gemm_tile_dma(const DmaOperand& A, const DmaOperand& B, int K, int m0, int n0,
                                               uint16_t* smem, Acc& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -258,13 +264,32 @@ __device__ __forceinline__ void gemm_tile_dma(const DmaOperand& A, const DmaOper
   const __amdgpu_buffer_rsrc_t ra = operand_rsrc(A), rb = operand_rsrc(B);
   const DmaLane la = dma_lane(m0, A, wave, lane), lb = dma_lane(n0, B, wave, lane);
   dma_issue(ra, rb, la, lb, 0, smem, wave);
+  // L2 warm-up.  A fifth of a slice's lines miss L2 (the 32 workgroups resident on an XCD form an
+  // 8 x 4 block of tiles: 12 operand slices for 32 tiles), and loads return in order, so one late
+  // line holds back everything queued behind it.  Each slice is therefore touched two slices
+  // early with one 4-byte load per 128-byte line (sunk into a scratch corner of LDS), the lines
+  // shared out over the workgroups that will read them: wave 0 takes a quarter of the A rows
+  // (which quarter: by tile column), wave 4 an eighth of the B rows (by tile row).  The touch is
+  // issued late in the slice, when every wave's requests for the next slice are already queued
+  // ahead of it, and it may stay in flight across the next barrier (vmcnt(1)).
+  constexpr int kWarmAhead = 2;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform: the descriptor stays scalar
+  const bool warm_a = wave_u < 4, warm_wave = WARM && (wave_u & 3) == 0;
+  const __amdgpu_buffer_rsrc_t rw = warm_a ? ra : rb;
+  const int warm_row = warm_a ? m0 + ((n0 / kTile) & 3) * 64 + lane : n0 + ((m0 / kTile) & 7) * 32 + (lane & 31);
+  const uint32_t warm_off = uint32_t(int64_t(warm_row) * (warm_a ? A.ld : B.ld) * 2) + (warm_a ? 0u : uint32_t(lane >> 5) * 64u);
+  const uint32_t warm_kstep = uint32_t((warm_a ? A.kstep : B.kstep) * 2);
+  uint16_t* const warm_sink = smem + kWarmSinkOff / 2 + wave * 128;
   // One iteration = one 64-wide slice = four 16-wide steps of 8 MFMAs per wave.  The order is
   // pinned with scheduling barriers: both fragment sets of the first two steps are read up
   // front, the next slice is requested only after the first MFMA group (issuing the 8 loads
   // right after the barrier would hold back every wave's first MFMAs: measured 8 % slower),
   // and the fragment reads of steps 2 and 3 are interleaved one-to-one with MFMAs.
-  auto slice = [&](int kt, bool prefetch) {
-    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): slice kt landed, own LDS reads done
+  // warm: touch slice kt + kWarmAhead; warm_pending: the previous slice issued a touch.
+  auto slice = [&](int kt, bool prefetch, bool warm, bool warm_pending) {
+    // slice kt landed (the youngest load may be a touch: loads return in order), own LDS reads done
+    if (warm_pending && warm_wave) __builtin_amdgcn_s_waitcnt(0x0071);   // vmcnt(1) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);                             // vmcnt(0) lgkmcnt(0)
     AERO_CFENCE();
     __builtin_amdgcn_s_barrier();
     AERO_CFENCE();
@@ -278,7 +303,6 @@ __device__ __forceinline__ void gemm_tile_dma(const DmaOperand& A, const DmaOper
     frags_mma(f1, acc);
     frags_load(f1, st, 3, wm, wn, lane);
     frags_mma(f0, acc);
-    frags_mma(f1, acc);
     constexpr int kMfma = 0x008, kVmemRd = 0x020, kDsRd = 0x100;
     constexpr int kFragReads = kMB + kNB, kMfmas = kMB * kNB;
     __builtin_amdgcn_sched_group_barrier(kDsRd, 2 * kFragReads, 0);
@@ -293,10 +317,27 @@ __device__ __forceinline__ void gemm_tile_dma(const DmaOperand& A, const DmaOper
       }
       __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas - kFragReads, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas, 0);
+    if (WARM) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (warm && warm_wave)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, warm_sink, 4, warm_off + uint32_t(kt + kWarmAhead) * warm_kstep, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    frags_mma(f1, acc);
+    if (!WARM) __builtin_amdgcn_sched_group_barrier(kMfma, kMfmas, 0);
   };
-  for (int kt = 0; kt + 1 < nk; ++kt) slice(kt, true);
-  slice(nk - 1, false);
+  // Every call site passes constants, so that each copy of the slice is one scheduling region.
+  // Measured: worth 2-4 % per contraction from about 50 slices on, nothing or a small loss at 24.
+  constexpr int kWarmMinSlices = 32;
+  if (WARM && nk >= kWarmMinSlices) {   // slice kt touches slice kt + 2: all but the last two do
+    slice(0, true, true, false);
+    for (int kt = 1; kt + kWarmAhead < nk; ++kt) slice(kt, true, true, true);
+    slice(nk - 2, true, false, true);
+    slice(nk - 1, false, false, false);
+  } else {
+    for (int kt = 0; kt + 1 < nk; ++kt) slice(kt, true, false, false);
+    slice(nk - 1, false, false, false);
+  }
   __syncthreads();
 }
 
@@ -307,7 +348,7 @@ __device__ __forceinline__ void gemm_tile_auto(const uint16_t* __restrict__ A, i
   const bool fast = (K % kDK == 0) && (lda % 8 == 0) && (ldb % 8 == 0) &&
                     (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0) &&
                     ((int64_t(M) - 1) * lda + K) < (int64_t(1) << 31) && ((int64_t(N) - 1) * ldb + K) < (int64_t(1) << 31);
-  if (fast) gemm_tile_dma(operand_row_major(A, lda, M, K), operand_row_major(B, ldb, N, K), K, m0, n0, smem, acc);
+  if (fast) gemm_tile_dma<true>(operand_row_major(A, lda, M, K), operand_row_major(B, ldb, N, K), K, m0, n0, smem, acc);
   else gemm_tile(A, lda, M, B, ldb, N, K, m0, n0, smem, acc);
 }
 

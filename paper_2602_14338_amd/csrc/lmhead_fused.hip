@@ -600,7 +600,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
   const int k_len = max(0, min(vcK, (split + 1) * per * kDK) - k_begin);
   Acc acc;
   // both operands are K-slabs over the vocabulary: dz of this chunk, WT of the whole vocabulary
-  gemm_tile_dma(operand_slabs(dz + int64_t(k_begin / kDK) * T_pad * kDK, T_pad, k_len),
+  gemm_tile_dma<false>(operand_slabs(dz + int64_t(k_begin / kDK) * T_pad * kDK, T_pad, k_len),
                 operand_slabs(WT + int64_t((v0 + k_begin) / kDK) * H_pad * kDK, H_pad, k_len), k_len, m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -631,7 +631,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
   tile_of_block(tiles_v, tiles_h, tv, th);
   const int m0 = tv * kTile, n0 = th * kTile;
   Acc acc;
-  gemm_tile_dma(operand_slabs(dzT, VC, nact[1]), operand_slabs(hTc, H_pad, nact[1]), nact[1], m0, n0, smem, acc);
+  gemm_tile_dma<true>(operand_slabs(dzT, VC, nact[1]), operand_slabs(hTc, H_pad, nact[1]), nact[1], m0, n0, smem, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3;
 #pragma unroll
@@ -675,7 +675,8 @@ __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh
 }
 
 // the dz kernel stages a padded 256 x 264 bf16 tile in LDS after its main loop
-constexpr size_t kDzLdsBytes = size_t(kTile) * (kTile + 8) * 2 > kGemmLdsBytes ? size_t(kTile) * (kTile + 8) * 2 : kGemmLdsBytes;
+static_assert(size_t(kTile) * (kTile + 8) * 2 <= kWarmSinkOff, "the dz staging tile must end before the warm-up sink");
+constexpr size_t kDzLdsBytes = kGemmLdsBytes;
 
 static aero_status set_lds(const void* fn, size_t bytes = kGemmLdsBytes) {
   return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)) == hipSuccess
