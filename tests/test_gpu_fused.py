@@ -66,8 +66,9 @@ def rowwise_close(got, want, frac=1e-2):
     return (np.abs(got - want) <= frac * scale + 1e-30).all()
 
 
+# (300, 2112, 1000): 33 K slices, the contraction loop's L2 warm-up (from 32 slices on) is active
 FWD_SHAPES = [(256, 64, 256), (300, 64, 1000), (17, 72, 77), (512, 1536, 3000), (700, 512, 5001 - 1),
-              (1, 8, 1), (1100, 256, 4096)]
+              (1, 8, 1), (1100, 256, 4096), (300, 2112, 1000)]
 
 
 @pytest.mark.parametrize("T,H,V", FWD_SHAPES)
@@ -113,12 +114,16 @@ def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, 
     return ref, out
 
 
+# the last two reach 32 K slices in the recompute (H = 2112) and in the dweight contraction (> 2048 tokens
+# with gradient), where the loop warms L2 ahead of its operand requests
 @pytest.mark.parametrize("T,H,V", [(256, 64, 256), (300, 64, 1000), (17, 72, 77), (700, 512, 5000),
-                                   (512, 1536, 3000), (1100, 256, 4096)])
+                                   (512, 1536, 3000), (1100, 256, 4096), (300, 2112, 1000), (4500, 64, 600)])
 def test_fused_backward(gh, T, H, V):
     wl, h, W = make(T, H, V, sigma_w=2.0 / np.sqrt(H))
     ref, _ = check_bwd(gh, wl, h, W, dict())
     assert (ref["g"] != 0).any()
+    if T >= 4096:
+        assert (ref["g"] != 0).sum() > 2048
     check_bwd(gh, wl, h, W, dict(reject_enable=1, posterior_mode=1), dweight_dtype=torch.bfloat16, grad_scale=8.0)
 
 
