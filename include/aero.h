@@ -4,8 +4,9 @@
  *
  * Conventions (all entry points)
  *   - Every array pointer is a DEVICE pointer owned by the caller.  The library never
- *     allocates, frees or keeps device memory between calls; scratch comes from the
- *     caller's `workspace` (size it with aero_workspace_bytes; 256-byte aligned).
+ *     allocates or frees device memory; scratch comes from the caller's `workspace` (size it
+ *     with aero_workspace_bytes; 256-byte aligned).  The one exception is stated at
+ *     aero_grpo_loss_bwd_noalloc, which uses a fixed array inside the library instead.
  *   - Scalars, the parameter struct and the returned status live on the HOST.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and the call returns without synchronising.  Calls that share a workspace must be
@@ -37,7 +38,8 @@ enum {
   AERO_ERR_DTYPE = 3,      /* dtype code not supported by this call */
   AERO_ERR_ALIGN = 4,      /* pointer or leading dimension violates a stated alignment */
   AERO_ERR_WORKSPACE = 5,  /* workspace NULL, misaligned or smaller than aero_workspace_bytes */
-  AERO_ERR_HIP = 6         /* a HIP launch failed; hipGetLastError has the detail */
+  AERO_ERR_HIP = 6,        /* a HIP launch failed; hipGetLastError has the detail */
+  AERO_ERR_LIMIT = 7       /* size beyond the fixed capacity of an entry point that owns its scratch */
 };
 
 enum { AERO_F32 = 0, AERO_BF16 = 1 };
@@ -171,6 +173,32 @@ aero_status aero_grpo_loss_bwd(
     float* entropy_out /*nullable*/, float* lse_out /*nullable*/,
     void* dlogits /*nullable*/, int32_t* err_flag /*nullable*/,
     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * aero_grpo_loss_bwd for callers that cannot allocate device memory and so cannot bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and status codes as aero_grpo_loss_bwd, minus `workspace` /
+ * `workspace_bytes`: the scratch is a fixed array of device memory inside the library
+ * (9 * 4 * AERO_NOALLOC_MAX_T + 256 bytes, about 2.3 MB, held on every GPU the library runs on
+ * until the process ends).  The call allocates and frees nothing.
+ *   - T > AERO_NOALLOC_MAX_T returns AERO_ERR_LIMIT and enqueues nothing.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on the same GPU
+ *     (different streams, different threads) race; order them on one stream.  The array keeps the
+ *     previous call's contents; the call clears what it needs cleared itself.
+ *   - The first call on a device looks up the array's address on that device (and may load the
+ *     code object): make it once outside any graph capture.
+ */
+#define AERO_NOALLOC_MAX_T 65536
+aero_status aero_grpo_loss_bwd_noalloc(
+    const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld,
+    const int32_t* targets, const float* lse /*nullable*/, const float* entropy /*nullable*/,
+    const float* old_logprob, const int32_t* token_rollout,
+    const float* adv, const float* weight, int32_t R,
+    float eps_lo, float eps_hi, float grad_scale, float entropy_coef,
+    float kl_coef, const float* ref_logprob /*nullable*/,
+    float* loss, float* clip_frac /*nullable*/, float* logprob_out /*nullable*/,
+    float* entropy_out /*nullable*/, float* lse_out /*nullable*/,
+    void* dlogits /*nullable*/, int32_t* err_flag /*nullable*/, void* stream);
 
 /*
  * The same statistics, loss and gradients with the LM head fused in: logits are

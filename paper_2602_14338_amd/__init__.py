@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     AeroError,
     aero_group_advantage,
     aero_grpo_loss_bwd,
+    aero_grpo_loss_bwd_noalloc,
     aero_lmhead_logprob_fused,
     aero_logprob_fwd,
     aero_workspace_bytes,

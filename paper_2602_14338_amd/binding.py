@@ -66,6 +66,8 @@ def _load() -> C.CDLL:
     lib.aero_grpo_loss_bwd.restype = i32
     lib.aero_grpo_loss_bwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p, i32, f32, f32, f32, f32, f32, p,
                                        p, p, p, p, p, p, p, p, sz, p]
+    lib.aero_grpo_loss_bwd_noalloc.restype = i32
+    lib.aero_grpo_loss_bwd_noalloc.argtypes = lib.aero_grpo_loss_bwd.argtypes[:-3] + [p]
     lib.aero_lmhead_logprob_fused.restype = i32
     lib.aero_lmhead_logprob_fused.argtypes = [p, p, i64, i32, i32, p, p, p, p, p, p, p, p, i32, f32, f32, f32, f32,
                                               f32, p, p, p, p, p, i32, p, p, sz, p]
@@ -162,6 +164,28 @@ def aero_grpo_loss_bwd(logits, T: int, V: int, ld: int, targets, lse, old_logpro
         _ptr(err_flag, torch.int32, "err_flag"), _ptr(workspace, None, "workspace"),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(logits))
     _check(st, "aero_grpo_loss_bwd")
+
+
+def aero_grpo_loss_bwd_noalloc(logits, T: int, V: int, ld: int, targets, lse, old_logprob, token_rollout, adv, weight,
+                               R: int, eps_lo: float, eps_hi: float, grad_scale: float, loss, clip_frac,
+                               logprob_out, dlogits, err_flag=None, entropy_out=None, lse_out=None,
+                               entropy_coef: float = 0.0, entropy=None, kl_coef: float = 0.0,
+                               ref_logprob=None) -> None:
+    """aero_grpo_loss_bwd without a workspace argument: the library's own fixed scratch is used."""
+    if dlogits is not None and dlogits.dtype != logits.dtype:
+        raise AeroError("dlogits must have the dtype of logits")
+    st = _lib.aero_grpo_loss_bwd_noalloc(
+        _ptr(logits, None, "logits"), _dtype_code(logits), T, V, ld, _ptr(targets, torch.int32, "targets"),
+        _ptr(lse, torch.float32, "lse"), _ptr(entropy, torch.float32, "entropy"),
+        _ptr(old_logprob, torch.float32, "old_logprob"),
+        _ptr(token_rollout, torch.int32, "token_rollout"), _ptr(adv, torch.float32, "adv"),
+        _ptr(weight, torch.float32, "weight"), R, eps_lo, eps_hi, grad_scale, entropy_coef,
+        kl_coef, _ptr(ref_logprob, torch.float32, "ref_logprob"),
+        _ptr(loss, torch.float32, "loss"), _ptr(clip_frac, torch.float32, "clip_frac"),
+        _ptr(logprob_out, torch.float32, "logprob_out"), _ptr(entropy_out, torch.float32, "entropy_out"),
+        _ptr(lse_out, torch.float32, "lse_out"), _ptr(dlogits, None, "dlogits"),
+        _ptr(err_flag, torch.int32, "err_flag"), _stream(logits))
+    _check(st, "aero_grpo_loss_bwd_noalloc")
 
 
 def aero_lmhead_logprob_fused(hidden, weight, T: int, H: int, V: int, targets, logprob, entropy, lse,

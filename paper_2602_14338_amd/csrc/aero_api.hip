@@ -15,6 +15,7 @@ extern "C" const char* aero_status_string(aero_status s) {
     case AERO_ERR_ALIGN: return "pointer or leading dimension is misaligned";
     case AERO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case AERO_ERR_HIP: return "HIP launch failed";
+    case AERO_ERR_LIMIT: return "size exceeds the fixed capacity of this entry point";
     default: return "unknown status";
   }
 }

@@ -13,6 +13,8 @@
 // kernels with ENT = true read (a, b) per row; with c == 0 the ENT = false kernels run.
 // KL penalty (Eq. 2's beta term, per-token estimator exp(d) - d - 1 with d = log pi_ref(y) - log pi(y)):
 // a per-token scalar like the surrogate, so it only adds to the loss term and to g_t.
+#include <mutex>
+
 #include "aero_device.h"
 
 namespace aero {
@@ -44,8 +46,9 @@ struct LossWorkspace {
   int32_t* counter;  // [3] counters of the streaming single-pass kernel
 };
 constexpr size_t kAlign = 256;
-inline size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
-size_t loss_workspace_bytes(int64_t T) { return 9 * seg(T) + kAlign; }
+constexpr size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
+constexpr size_t loss_workspace_bytes_c(int64_t T) { return 9 * seg(T) + kAlign; }
+size_t loss_workspace_bytes(int64_t T) { return loss_workspace_bytes_c(T); }
 inline LossWorkspace carve(void* ws, int64_t T) {
   char* p = reinterpret_cast<char*>(ws);
   const size_t s = seg(T);
@@ -439,16 +442,14 @@ aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, c
   return launch_status();
 }
 
-}  // namespace aero
-
-extern "C" aero_status aero_grpo_loss_bwd(
+// The loss call proper; both entry points below end here.
+static aero_status loss_bwd_run(
     const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
     const float* lse, const float* entropy, const float* old_logprob, const int32_t* token_rollout,
     const float* adv, const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale,
     float entropy_coef, float kl_coef, const float* ref_logprob, float* loss, float* clip_frac, float* logprob_out,
     float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag, void* workspace, size_t workspace_bytes,
     void* stream) {
-  using namespace aero;
   const bool ent = entropy_coef != 0.f;
   if (!(entropy_coef == entropy_coef) || !(kl_coef == kl_coef)) return AERO_ERR_SHAPE;   // NaN coefficient
   if (kl_coef != 0.f && T > 0 && !ref_logprob) return AERO_ERR_NULL;
@@ -515,4 +516,58 @@ extern "C" aero_status aero_grpo_loss_bwd(
     else dispatch_dlogits_dtype<false>(dtype, vec, logits, T, V, ld, targets, lse, ws.g, nullptr, nullptr, dlogits, s);
   }
   return launch_status();
+}
+
+// ---------------------------------------------------------------- library-owned scratch
+// For callers that cannot allocate: the workspace of a loss call of up to kStaticMaxT token rows
+// lives in device memory that belongs to the loaded code object.  Every GPU holds its own copy of
+// the array at its own address, so the address is looked up once per device, with that device
+// current, and only that pointer is ever handed to a kernel or a copy.
+constexpr int64_t kStaticMaxT = AERO_NOALLOC_MAX_T;
+constexpr size_t kStaticScratchBytes = loss_workspace_bytes_c(kStaticMaxT);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static aero_status static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AERO_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return AERO_ERR_HIP;
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return AERO_OK;
+}
+
+}  // namespace aero
+
+extern "C" aero_status aero_grpo_loss_bwd(
+    const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
+    const float* lse, const float* entropy, const float* old_logprob, const int32_t* token_rollout,
+    const float* adv, const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale,
+    float entropy_coef, float kl_coef, const float* ref_logprob, float* loss, float* clip_frac, float* logprob_out,
+    float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag, void* workspace, size_t workspace_bytes,
+    void* stream) {
+  return aero::loss_bwd_run(logits, dtype, T, V, ld, targets, lse, entropy, old_logprob, token_rollout, adv, weight, R,
+                            eps_lo, eps_hi, grad_scale, entropy_coef, kl_coef, ref_logprob, loss, clip_frac,
+                            logprob_out, entropy_out, lse_out, dlogits, err_flag, workspace, workspace_bytes, stream);
+}
+
+extern "C" aero_status aero_grpo_loss_bwd_noalloc(
+    const void* logits, int32_t dtype, int64_t T, int32_t V, int64_t ld, const int32_t* targets,
+    const float* lse, const float* entropy, const float* old_logprob, const int32_t* token_rollout,
+    const float* adv, const float* weight, int32_t R, float eps_lo, float eps_hi, float grad_scale,
+    float entropy_coef, float kl_coef, const float* ref_logprob, float* loss, float* clip_frac, float* logprob_out,
+    float* entropy_out, float* lse_out, void* dlogits, int32_t* err_flag, void* stream) {
+  if (T > aero::kStaticMaxT) return AERO_ERR_LIMIT;
+  void* ws = nullptr;
+  const aero_status st = aero::static_scratch(&ws);
+  if (st != AERO_OK) return st;
+  return aero::loss_bwd_run(logits, dtype, T, V, ld, targets, lse, entropy, old_logprob, token_rollout, adv, weight, R,
+                            eps_lo, eps_hi, grad_scale, entropy_coef, kl_coef, ref_logprob, loss, clip_frac,
+                            logprob_out, entropy_out, lse_out, dlogits, err_flag, ws, aero::kStaticScratchBytes, stream);
 }

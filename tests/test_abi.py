@@ -38,8 +38,8 @@ def test_status_strings_and_workspace_sizes_on_host():
     from paper_2602_14338_amd import binding
     lib = ctypes.CDLL(library())
     lib.aero_status_string.restype = ctypes.c_char_p
-    seen = {lib.aero_status_string(i) for i in range(7)}
-    assert len(seen) == 7 and lib.aero_status_string(99) == b"unknown status"
+    seen = {lib.aero_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and lib.aero_status_string(99) == b"unknown status"
     assert aero.aero_workspace_bytes(binding.OP_GROUP_ADVANTAGE, T=10) == 0
     assert aero.aero_workspace_bytes(binding.OP_LOGPROB_FWD, T=10, V=100) == 0
     a = aero.aero_workspace_bytes(binding.OP_GRPO_LOSS_BWD, T=16384, V=151936)
