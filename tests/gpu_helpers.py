@@ -93,10 +93,39 @@ def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv,
                 lse=lse_out)
 
 
+# Loss tolerance.  Stated for the method: 1e-4 relative.  It is applied as stated whenever the
+# reference is well conditioned: sum_t |term_t| <= CANCEL_RATIO_STRICT * |loss|.  With
+# group-standardised advantages (Eq. 1) the per-token terms of Eq. 2 cancel almost exactly when the
+# ratio is near 1, so the total can be orders of magnitude smaller than its terms; each term
+# carries the fp32 rounding of its log-probability (an ulp of a value near 10 is about 1e-6), and
+# that error does not shrink with the total.  Only in that case (ratio above the threshold) the
+# bound gains 2^-22 * sum_t |term_t|.
+CANCEL_RATIO_STRICT = 16.0
+
+
+def cancel_ratio(loss_ref, loss_terms):
+    total = float(np.abs(np.asarray(loss_terms, np.float64)).sum())
+    return total / abs(float(loss_ref)) if float(loss_ref) != 0.0 else (np.inf if total > 0 else 0.0)
+
+
 def loss_bound(loss_ref, loss_terms):
-    """Allowed |loss - loss_ref|: 1e-4 relative, plus fp32 rounding relative to the sum of the
-    per-token magnitudes.  With group-standardised advantages (Eq. 1) the per-token terms of
-    Eq. 2 cancel almost exactly when the ratio is near 1, so the total can be orders of magnitude
-    smaller than its terms; each term carries the fp32 rounding of its log-probability (an ulp
-    of a value near 10 is about 1e-6), and that error does not shrink with the total."""
-    return 1e-4 * abs(float(loss_ref)) + 2.0 ** -22 * float(np.abs(np.asarray(loss_terms, np.float64)).sum())
+    """Allowed |loss - loss_ref| (see the comment above)."""
+    strict = 1e-4 * abs(float(loss_ref))
+    if cancel_ratio(loss_ref, loss_terms) <= CANCEL_RATIO_STRICT:
+        return strict
+    return strict + 2.0 ** -22 * float(np.abs(np.asarray(loss_terms, np.float64)).sum())
+
+
+def assert_loss(got, loss_ref, loss_terms, strict=False):
+    """strict=True: the case is meant to be well conditioned, so the pure 1e-4 relative bound
+    must be the one in force."""
+    ratio = cancel_ratio(loss_ref, loss_terms)
+    if strict:
+        assert ratio <= CANCEL_RATIO_STRICT, "not a well-conditioned case: sum|term| / |loss| = %.3g" % ratio
+    bound = loss_bound(loss_ref, loss_terms)
+    diff = abs(float(got) - float(loss_ref))
+    assert diff <= bound, ("loss %.9e, reference %.9e: |diff| %.3e > bound %.3e (%s; sum|term| / |loss| = %.3g)"
+                           % (float(got), float(loss_ref), diff, bound,
+                              "1e-4 relative" if ratio <= CANCEL_RATIO_STRICT else "1e-4 relative + 2^-22 sum|term|",
+                              ratio))
+    return ratio

@@ -195,9 +195,14 @@ def elt_rounding(dtype, ref_abs):
 
 
 def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
-                   expect_clip=False, stats=False, entropy_coef=0.0, kl_coef=0.0):
+                   expect_clip=False, stats=False, entropy_coef=0.0, kl_coef=0.0, adv_map=None, strict_loss=False):
+    """adv_map: replaces the group-relative advantages by adv_map(adv) before both sides see them
+    (supplied advantages; e.g. abs makes every term of the loss carry one sign).
+    strict_loss: the loss must meet the pure 1e-4 relative bound (well-conditioned case)."""
     host = wl.logits_rows(0, wl.T)
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
+    if adv_map is not None:
+        ga["adv"] = adv_map(ga["adv"].astype(np.float32)).astype(np.float64)
     active = (wl.token_rollout >= 0).astype(np.uint8)
     lp_ref, ent_ref, lse_ref = orc.logprob_fwd(host, wl.dtype, wl.V, wl.targets, active)
     old = ai.draw_old_logprob(lp_ref, wl.seed, sigma=sigma_old)
@@ -217,7 +222,7 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
                           kl_coef=kl_coef, ref_logprob=ref_lp)
     assert out["err"] == 0
     loss = out["loss"].item()
-    assert abs(loss - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"]), (loss, ref["loss"])
+    gh.assert_loss(loss, ref["loss"], ref["loss_terms"], strict=strict_loss)
     assert abs(out["clip_frac"].item() - ref["clip_frac"]) < 1e-6
     if expect_clip:
         assert 0.02 < ref["clip_frac"] < 0.98
@@ -337,6 +342,49 @@ def test_loss_bwd_cfg3_reduced(gh):
     check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, expect_clip=True)
 
 
+def test_streaming_kernel_optional_terms_several_rows_per_workgroup(gh):
+    """V = 151936 with 320 rows: more rows than compute units, so the persistent workgroups of the
+    streaming single-pass kernel refill their slots with a second row and draw it from the row
+    counter, here in the variant that carries the optional terms (entropy bonus, Table 8; KL
+    penalty, Eq. 2's beta term) and with the gradient written over the logits."""
+    def wl():
+        return ai.make_config("cfg3", V=151936, T=320, Q=64, len_lo=1, len_hi=12)
+    ref, _ = check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, entropy_coef=0.02, expect_clip=True)
+    assert ((ref["g"] == 0) & (ref["e"] != 0)).any()
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, kl_coef=0.04, stats=True)
+    ref, _ = check_loss_bwd(gh, wl(), dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=False,
+                            kl_coef=0.04, entropy_coef=1e-3, inplace=True, grad_scale=4.0)
+    assert (ref["e"] == 0).any() and (ref["e"] != 0).any()      # dropped rollouts: rows with neither term
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, inplace=True)      # plain variant, in place
+    check_loss_bwd(gh, wl(), dict(reject_enable=1), use_oracle_lse=False, inplace=True, stats=True)
+
+
+# Well-conditioned losses: every term carries one sign, so nothing cancels and the stated
+# tolerance (1e-4 relative) is enforced with no rounding floor.
+@pytest.mark.parametrize("cfg,kw", [("cfg1", dict()),
+                                    ("cfg2", dict(V=151936, ld=151936, slots=6, len_lo=1, len_hi=6)),
+                                    ("cfg3", dict(V=151936, T=320, Q=64, len_lo=1, len_hi=12)),
+                                    ("cfg2", dict(V=4999, ld=4999, slots=10, len_lo=1, len_hi=10))])
+def test_loss_strict_tolerance_one_sign_advantages(gh, cfg, kw):
+    for route in (True, False):   # statistics given / computed in the call (single pass where it applies)
+        check_loss_bwd(gh, ai.make_config(cfg, **kw), dict(), sigma_old=0.3, use_oracle_lse=route, expect_clip=True,
+                       adv_map=lambda a: np.abs(a) + np.float32(0.25), strict_loss=True)
+        check_loss_bwd(gh, ai.make_config(cfg, **kw), dict(), sigma_old=0.05, use_oracle_lse=route,
+                       adv_map=lambda a: -np.abs(a) - np.float32(0.25), strict_loss=True)
+
+
+@pytest.mark.parametrize("cfg,kw", [("cfg1", dict()), ("cfg3", dict(V=151936, T=320, Q=64, len_lo=1, len_hi=12))])
+def test_loss_strict_tolerance_posterior_mode(gh, cfg, kw):
+    """Every group all-wrong: in posterior mode (Strategy 2) each kept rollout gets the same negative
+    advantage (-1/3 at n = 8 with the uniform prior), the loss is a sum of one-signed terms."""
+    for route in (True, False):
+        wl = ai.make_config(cfg, **kw)
+        wl.rewards[:] = 0.0
+        ref, _ = check_loss_bwd(gh, wl, dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=route,
+                                expect_clip=True, strict_loss=True)
+        assert (ref["g"] != 0).any() and ref["loss"] > 0
+
+
 def test_loss_is_run_to_run_identical_and_loss_only_mode(gh):
     wl = ai.make_config("cfg3", V=8000, T=3000, Q=64, len_lo=1, len_hi=40)
     host = wl.logits_rows(0, wl.T)
@@ -364,6 +412,62 @@ def test_bad_rollout_index_and_empty_batch(gh):
     out = gh.run_loss_bwd(d[:0], 0, wl.V, wl.ld, np.zeros(0, np.int32), None, np.zeros(0, np.float32),
                           np.zeros(0, np.int32), ga["adv"], ga["weight"])
     assert out["loss"].item() == 0.0 and out["clip_frac"].item() == 0.0
+
+
+def test_raw_c_abi_call_without_the_binding(gh):
+    """aero_logprob_fwd called through ctypes directly: plain device addresses and sizes, the NULL
+    (default) stream, status code returned; results against the checker."""
+    import ctypes as C
+    from paper_2602_14338_amd import binding
+    lib = C.CDLL(binding.library_path())
+    p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.aero_logprob_fwd.restype = i32
+    lib.aero_logprob_fwd.argtypes = [p, i32, i64, i32, i64, p, p, p, p, p, p, p]
+    wl = ai.make_config("cfg2", V=4999, ld=5008, slots=5, len_lo=1, len_hi=5)
+    host = wl.logits_rows(0, wl.T)
+    ref = orc.logprob_fwd(host, "bf16", wl.V, wl.targets)
+    z = gh.logits_to_dev(host, "bf16")
+    tg = gh.dev(wl.targets)
+    lp, ent, lse = (torch.full((wl.T,), 7.0, device=gh.DEV) for _ in range(3))
+    torch.cuda.synchronize()
+    st = lib.aero_logprob_fwd(z.data_ptr(), 1, wl.T, wl.V, wl.ld, tg.data_ptr(), None, lp.data_ptr(), ent.data_ptr(),
+                              lse.data_ptr(), None, None)
+    assert st == 0
+    torch.cuda.synchronize()
+    for got, want in ((lp, ref[0]), (ent, ref[1]), (lse, ref[2])):
+        assert np.abs(got.cpu().numpy().astype(np.float64) - want).max() <= LP_TOL
+    assert lib.aero_logprob_fwd(z.data_ptr(), 1, wl.T, wl.V, wl.V - 1, tg.data_ptr(), None, lp.data_ptr(), None,
+                                lse.data_ptr(), None, None) == 2      # AERO_ERR_SHAPE: ld < V
+    assert lib.aero_logprob_fwd(z.data_ptr(), 5, wl.T, wl.V, wl.ld, tg.data_ptr(), None, lp.data_ptr(), None,
+                                lse.data_ptr(), None, None) == 3      # AERO_ERR_DTYPE
+
+
+def test_ignored_rows_are_not_flagged(gh):
+    """Padding rows (rollout index -1) and rows switched off with row_active may hold anything in
+    their other fields, e.g. a sampled-token id past the vocabulary: no error bit, zero outputs.
+    Covers the forward call, the two-call loss route, and both single-pass kernels."""
+    for V, slots in ((512, 6), (32768, 6), (151936, 4)):
+        wl = ai.make_config("cfg2", V=V, slots=slots, len_lo=1, len_hi=slots - 1)
+        host = wl.logits_rows(0, wl.T)
+        pad = wl.token_rollout < 0
+        assert pad.any()
+        tg = wl.targets.copy()
+        tg[pad] = V + 7
+        ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, None, AdvParams())
+        d = gh.logits_to_dev(host, wl.dtype)
+        lp, ent, lse, err = gh.run_fwd(d, wl.T, wl.V, wl.ld, tg, (~pad).astype(np.uint8))
+        assert err == 0 and not lp[torch.from_numpy(pad).to(gh.DEV)].any()
+        _, _, _, err = gh.run_fwd(d, wl.T, wl.V, wl.ld, tg, None)      # not switched off: flagged
+        assert err == 2
+        old = np.full(wl.T, -12.0, np.float32)
+        for lse_arg in (lse, None):
+            out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, tg, lse_arg, old, wl.token_rollout, ga["adv"], ga["weight"])
+            assert out["err"] == 0
+            assert not out["dlogits"][torch.from_numpy(pad).to(gh.DEV)].float().any()
+        tr = wl.token_rollout.copy()
+        tr[~pad] = np.where(np.arange((~pad).sum()) % 3 == 0, wl.R + 1, tr[~pad])   # real bad indices are flagged
+        out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, tg, None, old, tr, ga["adv"], ga["weight"])
+        assert out["err"] == 4
 
 
 def test_host_side_argument_errors(gh):

@@ -64,7 +64,7 @@ def test_step_matches_checker(gh, mode):
     torch.cuda.synchronize()
     assert int(err.item()) == 0 and losses.shape == (n_mb,)
     total = losses.double().sum().item()
-    assert abs(total - ref["loss"]) <= gh.loss_bound(ref["loss"], ref["loss_terms"])
+    gh.assert_loss(total, ref["loss"], ref["loss_terms"])
     got = dz.view(T, V).cpu().numpy().astype(np.float64)
     # scale of a row: |g_t| for the surrogate and the KL term, |e_t| (1 + H_t) for the entropy term
     scale = np.abs(ref["g"]) + np.abs(ref["e"]) * (1.0 + ent_ref)

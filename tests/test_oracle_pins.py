@@ -505,6 +505,35 @@ def test_clip_edge_counts_as_unclipped():
         assert unclipped and g == -0.5 * A * rho
 
 
+def test_clip_fraction_counted_by_hand():
+    """clip_frac = clipped tokens / tokens with a non-zero advantage (and weight), counted by hand:
+    8 token rows; rollout 0 (A = +1) has ratios 1.0, 1.5 (clipped: above 1 + eps), 0.5 (not clipped:
+    below the range but A > 0 keeps the unclipped branch); rollout 1 (A = -2) has ratios 0.5
+    (clipped: below 1 - eps), 1.5 (not clipped for A < 0); rollout 2 has A = 0 (two tokens, one with
+    a wild ratio) and one padding row: neither counts in the denominator.  2 of 5."""
+    V = 6
+    rng = np.random.default_rng(3)
+    z = rng.normal(size=(8, V))
+    y = np.array([0, 1, 2, 3, 4, 5, 0, 1], np.int32)
+    tr = np.array([0, 0, 0, 1, 1, 2, 2, -1], np.int32)
+    ratios = np.array([1.0, 1.5, 0.5, 0.5, 1.5, 9.0, 1.0, 9.0])
+    lp = np.array([orc.logprob_row(z[t], y[t])[0] for t in range(8)])
+    old = lp - np.log(ratios)
+    adv, w = np.array([1.0, -2.0, 0.0]), np.array([0.5, 0.25, 0.125])
+    out = orc.grpo_loss_bwd(None, "f64", V, y, old, tr, adv, w, 0.2, 0.2, z64=z)
+    assert out["clip_frac"] == 2 / 5
+    assert [bool(x) for x in out["g"] != 0] == [True, False, True, False, True, False, False, False]
+    # loss by hand: -sum w min(rho A, clip(rho) A)
+    want = -(0.5 * (1.0 + 1.2 + 0.5) + 0.25 * (-2.0) * (0.8 + 1.5))
+    assert abs(out["loss"] - want) < 1e-12
+    # a rollout with weight 0 leaves the count as well: 1 of 2
+    out = orc.grpo_loss_bwd(None, "f64", V, y, old, tr, adv, np.array([0.0, 0.25, 0.125]), 0.2, 0.2, z64=z)
+    assert out["clip_frac"] == 1 / 2
+    # asymmetric range: eps_hi = 0.6 un-clips the 1.5 of rollout 0 -> 1 of 5
+    out = orc.grpo_loss_bwd(None, "f64", V, y, old, tr, adv, w, 0.2, 0.6, z64=z)
+    assert out["clip_frac"] == 1 / 5
+
+
 def test_on_policy_loss_is_minus_mean_advantage():
     """With rho = 1 everywhere Eq. 2 gives J = mean over queries of the group mean of the
     advantages; arbitrary advantages are supplied, weights come from the curation step."""
