@@ -13,12 +13,17 @@
  *     ordered on one stream.
  *   - Outputs are fully overwritten.  Nullable arguments are marked.
  *   - Shape errors that can be seen from host scalars return a status code and enqueue
- *     nothing.  Errors that depend on device data (a sampled-token id outside the
- *     vocabulary, a non-binary reward where binary ones are required, a rollout index
- *     outside [0, R)) never fault: the offending row / group is treated as ignored and a
- *     bit is OR-ed into the optional device word `err_flag`, which the caller zeroes.
+ *     nothing.  Errors that depend on device data never fault; a bit is OR-ed into the
+ *     optional device word `err_flag`, which the caller zeroes:
+ *       a sampled-token id >= V or a rollout index >= R: the token row is treated as ignored;
+ *       a reward other than 0 or 1 where binary ones are required: the group is still
+ *       processed, with every reward other than exactly 1 counted as incorrect.
  *   - "Ignored row": a token row with a negative sampled-token id, a negative rollout
- *     index, or row_active == 0.  It is not read; its outputs are 0 (gradient rows +0).
+ *     index, or row_active == 0.  It is not read, its outputs are 0 (gradient rows +0), and
+ *     nothing about it is flagged, whatever its other fields hold.
+ *   - Logits (and hidden states / weights) must be finite.  An infinite or NaN logit gives NaN
+ *     statistics for its row (the entropy term contains 0 * inf); vocabulary masking with -inf
+ *     is not part of the policy the paper defines (App. C).
  */
 #ifndef AERO_H
 #define AERO_H
@@ -204,6 +209,12 @@ aero_status aero_grpo_loss_bwd_noalloc(
  * The same statistics, loss and gradients with the LM head fused in: logits are
  * z = hidden @ weight^T (no bias, fp32 accumulation of bf16 products) and are never
  * written to memory as a [T, V] tensor.
+ *
+ * Defines: App. C (the policy is the softmax of the model's final linear layer: pi = softmax(h W^T),
+ * temperature 1, Table 8); Eq. 2 (clipped surrogate over the tokens of the kept rollouts, weights
+ * 1/N and 1/|o_i|, optional - beta D_KL term); App. A.1 (grad rho = rho grad log pi, clipped tokens
+ * contribute nothing, d log pi(y) / d z_j = 1[j = y] - pi_j), carried one step further through
+ * z = h W^T: dhidden = dz W, dweight = dz^T h.
  *
  * hidden   bf16 [T, H] row-major, weight bf16 [V, H] row-major, both 16-byte aligned, H % 8 == 0.
  * Forward outputs  logprob[T], lse[T] f32, entropy[T] f32 or NULL.

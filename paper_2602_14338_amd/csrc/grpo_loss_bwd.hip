@@ -93,9 +93,11 @@ __global__ __launch_bounds__(256) void k_token_terms(
   const int y = targets[t];
   float g = 0.f, term = 0.f, lp = 0.f, ea = 0.f, eb = 0.f;
   int flag = 0;
-  if (i >= R || y >= V) {
+  if (i < 0 || y < 0) {
+    // padding / ignored row: whatever its other index holds is not looked at
+  } else if (i >= R || y >= V) {
     if (err_flag) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
-  } else if (i >= 0 && y >= 0) {
+  } else {
     const float A = adv[i], w = weight[i];
     if (w != 0.f && (A != 0.f || ent_coef != 0.f || kl_coef != 0.f)) {   // decided before the ratio is touched
       if constexpr (LP_GIVEN) {

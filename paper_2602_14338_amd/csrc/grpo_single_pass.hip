@@ -60,7 +60,9 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
 
   if (!need) {
     if (tid == 0) {
-      if ((i >= R || y >= V) && err_flag) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
+      // padding / ignored rows (a negative index) are not flagged, whatever their other index holds
+      if (i >= 0 && y >= 0 && (i >= R || y >= V) && err_flag)
+        atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
       g_out[t] = 0.f;
       term_out[t] = 0.f;
       flag_out[t] = 0;
@@ -398,7 +400,8 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     if (tid == 0) {
       if (!cur.valid && err_flag) {
         const int i = token_rollout[t];
-        if (i >= R || cur.y >= V) atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
+        if (i >= 0 && cur.y >= 0 && (i >= R || cur.y >= V))   // padding / ignored rows are not flagged
+          atomicOr(err_flag, i >= R ? AERO_DERR_BAD_ROLLOUT : AERO_DERR_BAD_TARGET);
       }
       g_out[t] = g;
       term_out[t] = term;

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(NT) void k_logprob_fwd(
       logprob[t] = 0.f;
       lse_out[t] = 0.f;
       if (entropy) entropy[t] = 0.f;
-      if (y >= V && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
+      // a row the caller switched off is ignored whatever its target holds
+      if (y >= V && (row_active == nullptr || row_active[t] != 0) && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
     }
     return;
   }
