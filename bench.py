@@ -1,34 +1,42 @@
 #!/usr/bin/env python3
-"""Throughput of the logits path of the GRPO update on one MI355X.
+"""Throughput of the GRPO / AERO per-token hot path on one MI355X.
 
 One step = one pass of the hot path over one synthetic micro-batch with inputs resident in
-HBM: group advantages -> softmax statistics (log-prob, entropy, log-partition) ->
-clipped loss + dlogits.  Default workload: the Qwen2.5-Math-1.5B-shaped micro-batch
-(2 queries x 8 rollouts x 1024 right-padded slots, V = 151936, bf16 logits).
+HBM: group advantages -> softmax statistics (log-prob, entropy, log-partition) -> clipped loss
++ gradient.  The headline workload is the Qwen2.5-Math-1.5B-shaped micro-batch (cfg2: 2 queries
+x 8 rollouts x 1024 right-padded slots, V = 151936, bf16 logits).
 
-Prints one JSON line: tokens/s (valid token rows per second), the roofline of the dominant
-kernel measured with events on the launch stream, and the float64 CPU checker timed on a
-bounded sample of the same workload as a baseline.
+Prints ONE JSON line.  Its top level is the headline workload: tokens/s (valid token rows per
+second), the roofline of the dominant kernel measured with events on the launch stream, and the
+float64 CPU checker timed on a bounded sample of the same workload as a baseline.  Under
+"extra" the same process measures, each with its own roofline and CPU baseline: cfg2 with every
+slot valid, the AERO-pruned ragged batch (cfg3) and the two LM-head-fused workloads (cfg4,
+cfg5).  `--workload X` measures X alone.
 """
 import argparse
 import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 
 # HBM bytes per launch of the single-pass kernel on cfg2 from hardware counters (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for an elementwise copy of known size;
-# see profiles/logits_path_cfg2_hbm_traffic.txt).  Valid only for the kernel sources it was
-# measured on: the figure is reported only while their hash still matches.
+# see profiles/logits_path_cfg2_hbm_traffic.txt).  Not a measurement of this run: a figure from
+# that profile, valid only for the kernel sources it was taken on, so it is reported only while
+# their hash still matches and is null otherwise.
 MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8595e+09, "sources_sha256": "c0ac81581d75430026bec98f21e8babfafb9d5822646f5689dfd4b07e6d03609"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
+TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of the same kernel sources "
+                "(profiles/logits_path_cfg2_hbm_traffic.txt), not of this run; null once the sources changed")
 
 
 def measured_traffic(workload):
@@ -46,10 +54,14 @@ def measured_traffic(workload):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5", "step"])
-    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=None,
+                    choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5", "step"],
+                    help="measure this workload alone (default: cfg2 as the headline plus the extras)")
+    ap.add_argument("--no-extras", action="store_true", help="headline workload only")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
+                    help="CPU time budget of one workload's checker baseline (headline; extras get half)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -59,6 +71,13 @@ def parse():
                     help="instead of the benchmark, time plain library kernels on this GPU (an elementwise copy, a "
                          "fill, a reduction, a bf16 matmul of the LM-head shape) as context for the roofline fractions")
     return ap.parse_args()
+
+
+def host_threads():
+    """Threads the CPU baseline may use: the machine's CPU share (OMP_NUM_THREADS when set), never
+    more than the cores that exist."""
+    want = int(os.environ.get("OMP_NUM_THREADS", "16") or 16)
+    return max(1, min(want, os.cpu_count() or 1))
 
 
 def machine_ceilings(torch):
@@ -117,31 +136,82 @@ def machine_ceilings(torch):
     print(json.dumps(out))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def median_ms(pairs):
+    return float(np.median([a.elapsed_time(b) for a, b in pairs]))
 
-    import torch
+
+# ----------------------------------------------------------------------------------------------
+# logits path (cfg1, cfg2, cfg2-dense, cfg3)
+# ----------------------------------------------------------------------------------------------
+
+def cpu_baseline_logits(wl, host_old, budget_s):
+    """The float64 checker as it stands (group advantages, forward statistics, loss + gradient) on
+    valid rows drawn from evenly spaced 64-row blocks of the same batch: first on one thread, then
+    with the rows shared out over a thread pool (numpy releases the GIL inside its row operations)."""
     import aero_inputs as ai
-    import paper_2602_14338_amd as aero
-    from paper_2602_14338_amd import binding
+    from oracle import aero_oracle as orc
+    T, V = wl.T, wl.V
+    B = ai.workloads.ROWS_PER_BLOCK
+    valid_mask = wl.token_rollout >= 0
+    blocks = [b for b in range((T + B - 1) // B) if valid_mask[b * B:(b + 1) * B].any()]
+    t0 = time.perf_counter()
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, orc.AdvParams(**wl.adv_params))
+    t_ga = time.perf_counter() - t0
+    a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+    eps = np.float32(wl.eps)
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
+    def rows_of(block_ids):
+        sel, parts = [], []
+        for b in block_ids:
+            r0, r1 = b * B, min(T, (b + 1) * B)
+            m = valid_mask[r0:r1]
+            sel.append(np.arange(r0, r1)[m])
+            parts.append(wl.logits_rows(r0, r1)[m])           # input generation: untimed
+        return np.concatenate(sel), np.concatenate(parts)
+
+    def work(sel, hz):
+        orc.logprob_fwd(hz, wl.dtype, V, wl.targets[sel])
+        orc.grpo_loss_bwd(hz, wl.dtype, V, wl.targets[sel], host_old[sel], wl.token_rollout[sel], a32, w32, eps, eps, 1.0)
+
+    # one thread: blocks until a third of the budget is spent
+    order = np.random.default_rng(0).permutation(len(blocks))
+    done1, t1, used = 0, 0.0, 0
+    while used < len(order) and t1 < budget_s / 3:
+        sel, hz = rows_of([blocks[order[used]]])
+        used += 1
+        t = time.perf_counter()
+        work(sel, hz)
+        t1 += time.perf_counter() - t
+        done1 += len(sel)
+    rate1 = done1 / t1
+    # all cores: a sample sized for the rest of the budget at perfect scaling (at most 4096 rows), shared out in
+    # pieces of 8 rows
+    threads = host_threads()
+    want = int(min(4096, max(threads * 8, rate1 * threads * budget_s * 2 / 3)))
+    ids = []
+    n = 0
+    for j in order[::-1]:             # from the other end of the same random order
+        if n >= want:
+            break
+        ids.append(blocks[j])
+        n += int(valid_mask[blocks[j] * B:(blocks[j] + 1) * B].sum())
+    sel, hz = rows_of(ids)
+    pieces = [(sel[i:i + 8], hz[i:i + 8]) for i in range(0, len(sel), 8)]
+    t = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda p: work(*p), pieces))
+    tn = time.perf_counter() - t
+    return {"value": len(sel) / (tn + t_ga), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "one_thread_value": done1 / (t1 + t_ga), "host_cpus_visible": os.cpu_count(),
+            "sample": "valid token rows from randomly chosen 64-row blocks of the same workload, all three steps "
+                      "(group advantages, statistics, loss + dlogits), numpy float64: %d rows on %d threads "
+                      "(rows shared out over a thread pool) in %.1f s; %d rows on one thread in %.1f s"
+                      % (len(sel), threads, tn, done1, t1)}
+
+
+def run_logits(args, name, mods, headline):
+    torch, ai, aero, binding = mods
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-
-    if args.machine_ceilings:
-        return machine_ceilings(torch)
-    name = args.workload
-    if name in ("cfg4", "cfg5"):
-        return bench_fused(args, torch, ai, aero, binding)
-    if name == "step":
-        return bench_step(args, torch, ai, aero, binding)
     wl = ai.make_config("cfg2" if name == "cfg2-dense" else name)
     if name == "cfg2-dense":   # same tensor shape, every slot a valid token
         wl.lengths[:] = wl.T // wl.R
@@ -210,7 +280,7 @@ def main():
     torch.cuda.synchronize()
     old_logprob = d(ai.draw_old_logprob(logprob.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps))
 
-    if args.calibration_copy:
+    if args.calibration_copy and headline:
         torch.neg(logits, out=dlogits)   # one elementwise kernel: reads and writes T*ld*elt bytes
     for _ in range(args.warmup):
         step_adv(); step_fwd(); step_bwd()
@@ -218,20 +288,21 @@ def main():
     torch.cuda.synchronize()
     K = args.steps
 
-    # ---- forward call + loss call (6 bytes per logit), K steps, for comparison ------------
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    # ---- forward call + loss call (6 bytes per logit), for comparison ---------------------
+    K2 = K if headline else min(K, 20)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K2)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(K):
+    for k in range(K2):
         ev[k][0].record(); step_adv()
         ev[k][1].record(); step_fwd()
         ev[k][2].record(); step_bwd()
         ev[k][3].record()
     torch.cuda.synchronize()
     wall2 = time.perf_counter() - t0
-    ms_adv = float(np.mean([ev[k][0].elapsed_time(ev[k][1]) for k in range(K)]))
-    ms_fwd = float(np.mean([ev[k][1].elapsed_time(ev[k][2]) for k in range(K)]))
-    ms_bwd = float(np.mean([ev[k][2].elapsed_time(ev[k][3]) for k in range(K)]))
+    ms_adv = median_ms([(e[0], e[1]) for e in ev])
+    ms_fwd = median_ms([(e[1], e[2]) for e in ev])
+    ms_bwd = median_ms([(e[2], e[3]) for e in ev])
     loss_two = loss.item()
 
     # ---- timed region: exactly K steps of the hot path (single pass over the logits) ------
@@ -243,9 +314,9 @@ def main():
         ev1[k][0].record(); step_single(); ev1[k][1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_single = float(np.mean([a.elapsed_time(b) for a, b in ev1]))
+    ms_single = median_ms(ev1)
     assert int(err.item()) == 0 and np.isfinite(loss.item())
-    assert abs(loss.item() - loss_two) <= 1e-5 * abs(loss_two)      # both routes give the same loss
+    assert abs(loss.item() - loss_two) <= 1e-5 * abs(loss_two) + 1e-12      # both routes give the same loss
 
     # ---- algorithmic bytes per launch ----------------------------------------------------
     n_valid = wl.n_valid
@@ -258,75 +329,60 @@ def main():
     fwd_bytes = n_valid * row_bytes
     bwd_bytes = n_grad * 2 * row_bytes + n_zero * row_bytes
     single_bytes = n_valid * row_bytes + T * row_bytes   # every valid row read once, every row written once
+    valid_only_bytes = 2 * n_valid * row_bytes           # padding rows' zero fill not credited
     fwd_gbs = fwd_bytes / (ms_fwd * 1e-3) / 1e9
     bwd_gbs = bwd_bytes / (ms_bwd * 1e-3) / 1e9
     single_gbs = single_bytes / (ms_single * 1e-3) / 1e9
-    ms_step = wall / K * 1e3
+    valid_only_gbs = valid_only_bytes / (ms_single * 1e-3) / 1e9
+    single_kernel = "k_row_stream" if V // 8 > 8 * 1024 else ("k_row_single_pass" if V >= 8192 else "k_logprob_fwd + k_dlogits")
+    traffic = measured_traffic(name)
     out = {
         "metric": "tokens/s, GRPO logprob+loss fwd/bwd at V=%d" % V,
         "value": n_valid * K / wall,
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_step,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "T_rows": T, "valid_tokens": n_valid, "V": V, "storage": wl.dtype,
                    "queries": Q, "rollouts": R, "signal_rows": g_rows, "grad_rows": n_grad,
                    "zero_fill_rows": n_zero, "clip_eps": wl.eps, "input_gen_s": round(gen_s, 1),
                    "step": "aero_group_advantage + aero_grpo_loss_bwd(lse=NULL, logprob/entropy/lse out)"},
-        "kernels_ms": {"group_advantage": ms_adv, "single_pass_loss_call": ms_single,
-                       "two_call_logprob_fwd": ms_fwd, "two_call_grpo_loss_bwd": ms_bwd},
-        "two_call_route": {"tokens_per_s": n_valid * K / wall2, "ms_per_step": wall2 / K * 1e3,
-                           "logprob_fwd_GBps": fwd_gbs, "dlogits_GBps": bwd_gbs},
-        "roofline": {"kernel": "k_row_stream (timed as the whole aero_grpo_loss_bwd call: counter preset + row order + k_row_stream + loss reduce)", "bound": "hbm",
-                     "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": single_gbs / HBM_PEAK_GBS,
-                     "algorithmic_bytes": single_bytes, "traffic": measured_traffic(name)},
+        "kernels_ms": {"statistic": "median over the timed calls", "group_advantage": ms_adv,
+                       "single_pass_loss_call": ms_single, "two_call_logprob_fwd": ms_fwd,
+                       "two_call_grpo_loss_bwd": ms_bwd},
+        "two_call_route": {"tokens_per_s": n_valid * K2 / wall2, "ms_per_step": wall2 / K2 * 1e3,
+                           "logprob_fwd_GBps": fwd_gbs, "dlogits_GBps": bwd_gbs,
+                           "logprob_fwd_frac": fwd_gbs / HBM_PEAK_GBS, "dlogits_frac": bwd_gbs / HBM_PEAK_GBS},
+        "roofline": {"kernel": "%s (timed as the whole aero_grpo_loss_bwd call: counter preset + row order + the "
+                               "row kernel + loss reduce; median of %d calls)" % (single_kernel, K),
+                     "bound": "hbm", "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": single_gbs / HBM_PEAK_GBS, "algorithmic_bytes": single_bytes,
+                     "accounting": "every valid row read once (2V bytes) + every row of the tensor written once "
+                                   "(2V bytes; rows without gradient are zero-filled)",
+                     "valid_rows_only": {"algorithmic_bytes": valid_only_bytes, "achieved": valid_only_gbs,
+                                         "frac": valid_only_gbs / HBM_PEAK_GBS,
+                                         "accounting": "4V bytes per valid row; the zero fill of padding rows is "
+                                                       "not credited"},
+                     "traffic": traffic, "traffic_source": TRAFFIC_NOTE if traffic is not None else None},
     }
-
-    # ---- CPU baseline: the float64 checker as it stands, on a bounded sample ---------------
     if not args.no_cpu_baseline:
-        from oracle import aero_oracle as orc
-        # sample = the valid rows of evenly spaced 64-row generation blocks
-        B = ai.workloads.ROWS_PER_BLOCK
-        valid_mask = wl.token_rollout >= 0
-        blocks = [b for b in range((T + B - 1) // B) if valid_mask[b * B:(b + 1) * B].any()]
-        n = min(args.cpu_sample_rows, int(valid_mask.sum()))
-        stride = max(1, int(len(blocks) * B / max(n, 1)))
-        host_old = old_logprob.cpu().numpy()
-        tc = 0.0
-        t_ga = time.perf_counter()
-        ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority,
-                                 orc.AdvParams(**wl.adv_params))
-        tc += time.perf_counter() - t_ga
-        a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
-        done = 0
-        for b in blocks[::stride]:
-            r0, r1 = b * B, min(T, (b + 1) * B)
-            sel = np.arange(r0, r1)[valid_mask[r0:r1]]
-            hz = wl.logits_rows(r0, r1)[valid_mask[r0:r1]]           # input generation: untimed
-            t1 = time.perf_counter()
-            orc.logprob_fwd(hz, wl.dtype, V, wl.targets[sel])
-            orc.grpo_loss_bwd(hz, wl.dtype, V, wl.targets[sel], host_old[sel], wl.token_rollout[sel], a32, w32,
-                              np.float32(wl.eps), np.float32(wl.eps), 1.0)
-            tc += time.perf_counter() - t1
-            done += len(sel)
-            if tc > 30.0 or done >= n:
-                break
-        out["cpu_baseline"] = {"value": done / tc, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-                               "sample": "%d valid token rows of the same workload (every %d-th 64-row block), "
-                                         "all three steps, numpy float64 single thread" % (done, stride)}
-    print(json.dumps(out))
+        out["cpu_baseline"] = cpu_baseline_logits(wl, old_logprob.cpu().numpy(),
+                                                  args.cpu_seconds if headline else args.cpu_seconds / 2)
+    return out
 
 
-MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+# ----------------------------------------------------------------------------------------------
+# one policy-update step through the logits path
+# ----------------------------------------------------------------------------------------------
 
-
-def bench_step(args, torch, ai, aero, binding):
+def bench_step(args, mods):
     """One policy-update step (256 queries x 16 rollouts, 35 % of the groups with all-equal
     rewards) through the logits path, micro-batch by micro-batch, with plain grouping and with
     AERO's curation.  Reports how many rollouts / tokens each mode trains on and the time of the
     curation call plus all loss / gradient calls.  One resident [mb_tokens, V] bf16 logits
     buffer serves every micro-batch (its content does not change the work done per row); the
     model forward / backward and rollout generation are outside this path."""
+    torch, ai, aero, binding = mods
     from paper_2602_14338_amd import step
     dev = "cuda:0"
     V, mb_tokens = 151936, 16384
@@ -375,7 +431,7 @@ def bench_step(args, torch, ai, aero, binding):
                      "tokens_with_signal": int(groups.lengths[rollouts][signal].sum()),
                      "micro_batches": int(plan.shape[0]), "ms": ms, "loss": float(losses.double().sum().item())}
     gen_tokens = int(groups.lengths.sum())
-    res = {
+    return {
         "metric": "ms per policy-update step on the logits path (256 queries x 16 rollouts, V=151936), AERO-curated",
         "value": out["aero"]["ms"], "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
         "ms_per_step": out["aero"]["ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
@@ -386,15 +442,60 @@ def bench_step(args, torch, ai, aero, binding):
         "token_ratio_aero_over_grpo": out["aero"]["tokens_trained"] / out["grpo"]["tokens_trained"],
         "time_ratio_aero_over_grpo": out["aero"]["ms"] / out["grpo"]["ms"],
     }
-    print(json.dumps(res))
 
 
-def bench_fused(args, torch, ai, aero, binding):
+# ----------------------------------------------------------------------------------------------
+# fused LM-head path (cfg4, cfg5)
+# ----------------------------------------------------------------------------------------------
+
+def cpu_baseline_fused(wl, h_rows, W_bits, host_old, a32, w32, budget_s):
+    """The float64 checker's fused definition (float64 product h W^T through the BLAS dgemm numpy
+    links, then statistics, loss, dz, dhidden = dz W and dweight = dz^T h) on a sample of token
+    rows of the same batch against the full weight matrix: with the BLAS's threads, then with one."""
+    from oracle import aero_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([int(i.get("num_threads", 1)) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+    except Exception:   # no control over the BLAS pool: report what it is given
+        threadpool_limits, blas_threads = None, host_threads()
+    T = wl.T
+    valid = np.nonzero(wl.token_rollout >= 0)[0]
+    eps = np.float32(wl.eps)
+    flop_per_row = 8.0 * wl.V * wl.H
+    # sample sizes from a nominal dgemm rate (20 GFLOP/s per thread), the conversions of W included in the time
+    n_all = int(np.clip(budget_s * 0.45 * 20e9 * blas_threads / flop_per_row, 16, 512))
+    n_one = int(np.clip(budget_s * 0.25 * 20e9 / flop_per_row, 4, 64))
+
+    def run(n):
+        sel = valid[np.linspace(0, len(valid) - 1, n).astype(np.int64)]
+        t = time.perf_counter()
+        orc.lmhead_fused(h_rows(sel), W_bits, wl.targets[sel], host_old[sel], wl.token_rollout[sel], a32, w32,
+                         eps, eps, 1.0)
+        return n, time.perf_counter() - t
+
+    n_a, t_a = run(n_all)
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            n_1, t_1 = run(n_one)
+    else:
+        n_1, t_1 = n_a, t_a
+    return {"value": n_a / t_a, "unit": "tokens/s", "cores": blas_threads, "kind": "oracle",
+            "one_thread_value": n_1 / t_1, "host_cpus_visible": os.cpu_count(),
+            "sample": "%d evenly spaced valid token rows of the same workload against the full [V, H] weight, the "
+                      "checker's fused definition (float64 product, statistics, loss, dz, dhidden, dweight), numpy "
+                      "float64 with %d BLAS threads in %.1f s; %d rows with one thread in %.1f s (each run also "
+                      "widens the whole weight matrix to float64, as the checker does)"
+                      % (n_a, blas_threads, t_a, n_1, t_1)}
+
+
+def run_fused(args, name, mods):
     """Fused LM-head workloads: one step = group advantages + fused forward + loss + dhidden/dweight."""
+    torch, ai, aero, binding = mods
     dev = "cuda:0"
-    wl = ai.make_config(args.workload)
+    wl = ai.make_config(name)
     T, H, V, R, Q = wl.T, wl.H, wl.V, wl.R, wl.Q
     t0 = time.time()
+    W_bits = wl.weight_rows(0, V, threads=args.gen_threads)
 
     def up_rows(gen, n, width):
         out = torch.empty((n, width), dtype=torch.bfloat16, device=dev)
@@ -404,7 +505,7 @@ def bench_fused(args, torch, ai, aero, binding):
         return out
 
     hidden = up_rows(wl.hidden_rows, T, H)
-    weight = up_rows(wl.weight_rows, V, H)
+    weight = torch.from_numpy(W_bits.view(np.int16)).to(dev).view(torch.bfloat16)
     gen_s = time.time() - t0
 
     def d(x):
@@ -442,11 +543,13 @@ def bench_fused(args, torch, ai, aero, binding):
     step_adv()
     step_fwd_only()
     torch.cuda.synchronize()
-    old_lp = d(ai.draw_old_logprob(lp.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps))
-    for _ in range(args.warmup):
+    host_old = ai.draw_old_logprob(lp.cpu().numpy(), wl.seed, sigma=0.05, eps_lo=wl.eps, eps_hi=wl.eps)
+    old_lp = d(host_old)
+    K = max(1, min(args.steps, 20 if H <= 2048 else 10))
+    W = max(1, min(args.warmup, 5 if H <= 2048 else 3))
+    for _ in range(W):
         step_adv(); step_full()
     torch.cuda.synchronize()
-    K = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
     t0 = time.perf_counter()
     for k in range(K):
@@ -454,37 +557,89 @@ def bench_fused(args, torch, ai, aero, binding):
         ev[k][0].record(); step_full(); ev[k][1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_fused = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ms_fused = median_ms(ev)
     # forward alone, for the split
-    ef = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(3)]
+    ef = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(max(3, K // 2))]
     for a, b in ef:
         a.record(); step_fwd_only(); b.record()
     torch.cuda.synchronize()
-    ms_fwd = float(np.mean([a.elapsed_time(b) for a, b in ef]))
+    ms_fwd = median_ms(ef)
     assert int(err.item()) == 0 and np.isfinite(loss.item())
 
-    adv_h = adv.cpu().numpy()
+    adv_h, wgt_h = adv.cpu().numpy(), wgt.cpu().numpy()
     tr = wl.token_rollout
     signal = int(((tr >= 0) & (adv_h[np.maximum(tr, 0)] != 0)).sum())
     n_grad = int(round(signal * (1.0 - clip.item())))
     flops = 2.0 * wl.n_valid * V * H + 6.0 * n_grad * V * H
     tf = flops / (ms_fused * 1e-3) / 1e12
-    tf_fwd = 2.0 * T * V * H / (ms_fwd * 1e-3) / 1e12
+    tf_fwd = 2.0 * wl.n_valid * V * H / (ms_fwd * 1e-3) / 1e12
     out = {
         "metric": "tokens/s, fused LM-head GRPO logprob+loss fwd/bwd at V=%d, H=%d" % (V, H),
-        "value": wl.n_valid * K / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "value": wl.n_valid * K / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "T": T, "H": H, "V": V, "queries": Q, "rollouts": R,
-                   "signal_rows": signal, "grad_rows": n_grad, "input_gen_s": round(gen_s, 1)},
-        "kernels_ms": {"fused_fwd_bwd_call": ms_fused, "fused_fwd_only_call": ms_fwd},
-        "roofline": {"kernel": "whole aero_lmhead_logprob_fused call (fwd + bwd), algorithmic flops "
-                               "2 T_valid V H + 6 T_grad V H", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
-        "roofline_fwd": {"kernel": "fused forward call", "bound": "mfma", "achieved": tf_fwd,
-                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf_fwd / MFMA_BF16_PEAK_TFLOPS,
-                         "traffic": None},
+        "config": {"workload": name, "T": T, "valid_tokens": wl.n_valid, "H": H, "V": V, "queries": Q, "rollouts": R,
+                   "signal_rows": signal, "grad_rows": n_grad, "input_gen_s": round(gen_s, 1),
+                   "step": "aero_group_advantage + aero_lmhead_logprob_fused (forward + loss + dhidden + dweight)"},
+        "kernels_ms": {"statistic": "median over the timed calls", "fused_fwd_bwd_call": ms_fused,
+                       "fused_fwd_only_call": ms_fwd},
+        "roofline": {"kernel": "whole aero_lmhead_logprob_fused call (fwd + bwd; median of %d calls), algorithmic flops "
+                               "2 T_valid V H + 6 T_grad V H" % K, "bound": "mfma", "achieved": tf,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+                     "algorithmic_flops": flops, "traffic": None},
+        "roofline_fwd": {"kernel": "fused forward call (gather + k_fused_stats + combine), 2 T_valid V H", "bound": "mfma",
+                         "achieved": tf_fwd, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf_fwd / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
     }
+    if not args.no_cpu_baseline:
+        del dw, dh, ws
+        out["cpu_baseline"] = cpu_baseline_fused(wl, lambda sel: np.stack([wl.hidden_rows(int(t), int(t) + 1)[0] for t in sel]),
+                                                 W_bits, host_old, adv_h.astype(np.float32), wgt_h.astype(np.float32),
+                                                 args.cpu_seconds / 2)
+    return out
+
+
+def run_workload(args, name, mods, headline):
+    if name in ("cfg4", "cfg5"):
+        return run_fused(args, name, mods)
+    if name == "step":
+        return bench_step(args, mods)
+    return run_logits(args, name, mods, headline)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import aero_inputs as ai
+    import paper_2602_14338_amd as aero
+    from paper_2602_14338_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    mods = (torch, ai, aero, binding)
+
+    if args.machine_ceilings:
+        return machine_ceilings(torch)
+    if args.workload is not None:
+        print(json.dumps(run_workload(args, args.workload, mods, headline=True)))
+        return
+    out = run_workload(args, "cfg2", mods, headline=True)
+    if not args.no_extras:
+        out["extra"] = {}
+        for name in ("cfg2-dense", "cfg3", "cfg4", "cfg5"):
+            torch.cuda.empty_cache()
+            t0 = time.time()
+            res = run_workload(args, name, mods, headline=False)
+            res["bench_wall_s"] = round(time.time() - t0, 1)
+            out["extra"][name] = res
+            print("bench.py: %s done in %.1f s" % (name, res["bench_wall_s"]), file=sys.stderr, flush=True)
     print(json.dumps(out))
 
 
