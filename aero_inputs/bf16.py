@@ -1,4 +1,4 @@
-"""bfloat16 storage for generated inputs (bit patterns held in ``uint16`` arrays)."""
+"""bfloat16 / binary16 storage for generated inputs (bit patterns held in ``uint16`` arrays)."""
 import numpy as np
 
 
@@ -11,3 +11,8 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     lsb = (u >> np.uint32(16)) & np.uint32(1)
     r = u + np.uint32(0x7FFF) + lsb
     return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to IEEE binary16 (round-to-nearest-even), return the uint16 bits."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)

@@ -19,7 +19,7 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-from .bf16 import f32_to_bf16_bits
+from .bf16 import f32_to_bf16_bits, f32_to_f16_bits
 
 ROWS_PER_BLOCK = 64
 
@@ -43,7 +43,7 @@ def normal_rows(seed: int, stream: int, r0: int, r1: int, ncols: int, sigma: flo
                 threads: int = 1) -> np.ndarray:
     """Rows ``[r0, r1)`` of an i.i.d. N(0, sigma^2) matrix with ``ncols`` columns.
 
-    ``dtype`` is ``"f32"`` (float32 values) or ``"bf16"`` (uint16 bit patterns, RNE).
+    ``dtype`` is ``"f32"`` (float32 values), ``"bf16"`` or ``"f16"`` (uint16 bit patterns, RNE).
     Row ``r`` always comes from block ``r // ROWS_PER_BLOCK`` of the keyed stream, so
     the result does not depend on how the rows are requested.  With ``ld > ncols``
     the trailing columns hold +inf: they are not part of the matrix and a reader that
@@ -55,7 +55,7 @@ def normal_rows(seed: int, stream: int, r0: int, r1: int, ncols: int, sigma: flo
         out = np.empty((r1 - r0, ld), dtype=np_dt)
     assert out.shape == (r1 - r0, ld) and out.dtype == np_dt
     if ld > ncols:
-        out[:, ncols:] = np.inf if dtype == "f32" else np.uint16(0x7F80)
+        out[:, ncols:] = np.inf if dtype == "f32" else np.uint16(0x7F80 if dtype == "bf16" else 0x7C00)
 
     def do_block(b: int) -> None:
         lo, hi = b * ROWS_PER_BLOCK, (b + 1) * ROWS_PER_BLOCK
@@ -63,7 +63,8 @@ def normal_rows(seed: int, stream: int, r0: int, r1: int, ncols: int, sigma: flo
         x *= np.float32(sigma)
         s0, s1 = max(lo, r0), min(hi, r1)
         part = x[s0 - lo:s1 - lo]
-        out[s0 - r0:s1 - r0, :ncols] = part if dtype == "f32" else f32_to_bf16_bits(part)
+        out[s0 - r0:s1 - r0, :ncols] = (part if dtype == "f32" else
+                                        f32_to_bf16_bits(part) if dtype == "bf16" else f32_to_f16_bits(part))
 
     blocks = range(r0 // ROWS_PER_BLOCK, (r1 - 1) // ROWS_PER_BLOCK + 1) if r1 > r0 else []
     if threads > 1:
@@ -112,7 +113,7 @@ class _Groups:
 class LogitsWorkload(_Groups):
     name: str = ""
     seed: int = 0
-    dtype: str = "bf16"            # "bf16" | "f32"
+    dtype: str = "bf16"            # "bf16" | "f16" | "f32"
     T: int = 0
     V: int = 0
     ld: int = 0
@@ -236,8 +237,8 @@ def make_config(name: str, seed: Optional[int] = None, **ov):
 
     name   what it is                                            overrides (for smaller parity cases)
     cfg1   4 queries x 8 rollouts x 64 tokens, V=1024, fp32      V, L, ld
-    cfg2   2 queries x 8 rollouts, right-padded slots, bf16      V, slots, len_lo, len_hi, ld
-    cfg3   64 curated ragged groups packed into T rows, bf16     V, T, Q, len_lo, len_hi, ld
+    cfg2   2 queries x 8 rollouts, right-padded slots, bf16      V, slots, len_lo, len_hi, ld, dtype
+    cfg3   64 curated ragged groups packed into T rows, bf16     V, T, Q, len_lo, len_hi, ld, dtype
     cfg4   fused LM head, H=1536, groups of 8 packed into T      V, T, H, Q, len_lo, len_hi
     cfg5   fused LM head, H=3584, 128 ragged groups packed       V, T, H, Q, len_lo, len_hi
     The default seed is the configuration's ordinal minus one (cfg1 -> 0).
@@ -271,7 +272,7 @@ def make_config(name: str, seed: Optional[int] = None, **ov):
         wl = LogitsWorkload(
             Q=Q, R=Q * N, group_offsets=_offsets(sizes), rewards=rewards, lengths=lengths,
             keep_priority=_priority(seed, Q * N), adv_params=params,
-            name=name, seed=seed, dtype="bf16", T=T, V=V, ld=ov.pop("ld", V), sigma=3.0,
+            name=name, seed=seed, dtype=ov.pop("dtype", "bf16"), T=T, V=V, ld=ov.pop("ld", V), sigma=3.0,
             targets=_targets(seed, T, V), token_rollout=_padded_layout(lengths, slots))
     elif name == "cfg3":
         seed = 2 if seed is None else seed
@@ -282,7 +283,7 @@ def make_config(name: str, seed: Optional[int] = None, **ov):
         wl = LogitsWorkload(
             Q=Q, R=int(go[-1]), group_offsets=go, rewards=rewards, lengths=lengths,
             keep_priority=_priority(seed, int(go[-1])), adv_params=params,
-            name=name, seed=seed, dtype="bf16", T=T, V=V, ld=ov.pop("ld", V), sigma=3.0,
+            name=name, seed=seed, dtype=ov.pop("dtype", "bf16"), T=T, V=V, ld=ov.pop("ld", V), sigma=3.0,
             targets=_targets(seed, T, V), token_rollout=_packed_layout(rs, go, lengths, T))
     elif name in ("cfg4", "cfg5"):
         if name == "cfg4":

@@ -47,7 +47,10 @@ enum {
   AERO_ERR_LIMIT = 7       /* size beyond the fixed capacity of an entry point that owns its scratch */
 };
 
-enum { AERO_F32 = 0, AERO_BF16 = 1 };
+/* Storage types of logits / dlogits.  AERO_F16 (IEEE binary16) is accepted by aero_logprob_fwd and
+ * aero_grpo_loss_bwd only; its gradient entries round to the fp16 grid (subnormals below 6.1e-5,
+ * zero below 3e-8): pass a grad_scale that lifts them, as with any fp16 gradient. */
+enum { AERO_F32 = 0, AERO_BF16 = 1, AERO_F16 = 2 };
 
 /* bits of the device error word */
 enum { AERO_DERR_NONBINARY_REWARD = 1, AERO_DERR_BAD_TARGET = 2, AERO_DERR_BAD_ROLLOUT = 4 };
@@ -114,7 +117,7 @@ aero_status aero_group_advantage(
  *   lse[t] = log sum_j exp z[t,j],  logprob[t] = z[t, targets[t]] - lse[t],
  *   entropy[t] = lse[t] - sum_j softmax(z[t])_j z[t,j]          (natural log, temperature 1)
  *
- * logits   [T, ld] row-major, dtype AERO_BF16 or AERO_F32, ld >= V; columns >= V are never
+ * logits   [T, ld] row-major, dtype AERO_BF16, AERO_F16 or AERO_F32, ld >= V; columns >= V are never
  *          read.  Any alignment works; rows whose base and ld*sizeof(elt) are multiples of
  *          16 bytes take the 128-bit load path.
  * targets  i32[T] sampled-token ids; row_active u8[T] or NULL.

@@ -56,11 +56,15 @@ class AdvParams:
 
 
 def widen(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Stored values -> float64, exactly.  dtype: "bf16" (uint16 bits), "f32", "f64"."""
+    """Stored values -> float64, exactly.  dtype: "bf16" or "f16" (uint16 bits), "f32", "f64"."""
     if dtype == "bf16":
         x = np.ascontiguousarray(x)
         assert x.dtype == np.uint16
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if dtype == "f16":      # IEEE binary16: every value is a float64 value
+        x = np.ascontiguousarray(x)
+        assert x.dtype == np.uint16
+        return x.view(np.float16).astype(np.float64)
     return np.asarray(x).astype(np.float64)
 
 

@@ -17,4 +17,5 @@ from .binding import (  # noqa: F401
     library_path,
     AERO_F32,
     AERO_BF16,
+    AERO_F16,
 )

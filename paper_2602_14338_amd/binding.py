@@ -12,7 +12,7 @@ from typing import Optional
 
 import torch
 
-AERO_F32, AERO_BF16 = 0, 1
+AERO_F32, AERO_BF16, AERO_F16 = 0, 1, 2
 OP_GROUP_ADVANTAGE, OP_LOGPROB_FWD, OP_GRPO_LOSS_BWD, OP_LMHEAD_FUSED = 0, 1, 2, 3
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaero_hip.so")
@@ -113,6 +113,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return AERO_BF16
     if t.dtype == torch.float32:
         return AERO_F32
+    if t.dtype == torch.float16:
+        return AERO_F16
     raise AeroError(f"unsupported dtype {t.dtype}")
 
 

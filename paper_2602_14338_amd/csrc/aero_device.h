@@ -29,6 +29,39 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
   return uint16_t(pack_bf16x2(x, 0.f) & 0xffffu);
 }
 
+// IEEE binary16 storage: widening is exact, narrowing rounds to nearest even (subnormals kept).
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float f16_to_f32(uint16_t b) {
+  _Float16 h;
+  __builtin_memcpy(&h, &b, 2);
+  return float(h);
+}
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  f16x2_t h = __builtin_convertvector(f, f16x2_t);
+  uint32_t w;
+  __builtin_memcpy(&w, &h, 4);
+  return w;
+}
+__device__ __forceinline__ uint16_t f32_to_f16(float x) { return uint16_t(pack_f16x2(x, 0.f) & 0xffffu); }
+
+// Storage type tags (the values of the public dtype codes) and what depends on them.
+constexpr int kF32 = AERO_F32, kBF16 = AERO_BF16, kF16 = AERO_F16;
+template <int DT> struct Storage {
+  static constexpr int kBytes = DT == kF32 ? 4 : 2;
+  static constexpr int kPerVec = 16 / kBytes;   // elements per 16-byte vector
+};
+template <int DT> __device__ __forceinline__ float load_elt(const void* row, int64_t j) {
+  if constexpr (DT == kBF16) return bf16_to_f32(reinterpret_cast<const uint16_t*>(row)[j]);
+  else if constexpr (DT == kF16) return f16_to_f32(reinterpret_cast<const uint16_t*>(row)[j]);
+  else return reinterpret_cast<const float*>(row)[j];
+}
+template <int DT> __device__ __forceinline__ void store_elt(void* row, int64_t j, float x) {
+  if constexpr (DT == kBF16) reinterpret_cast<uint16_t*>(row)[j] = f32_to_bf16(x);
+  else if constexpr (DT == kF16) reinterpret_cast<uint16_t*>(row)[j] = f32_to_f16(x);
+  else reinterpret_cast<float*>(row)[j] = x;
+}
+
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
@@ -115,6 +148,41 @@ __device__ __forceinline__ void unpack8(const u32x4_t& v, float (&z)[8]) {
   z[2] = bf16_lo(v.y); z[3] = bf16_hi(v.y);
   z[4] = bf16_lo(v.z); z[5] = bf16_hi(v.z);
   z[6] = bf16_lo(v.w); z[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ void unpack8_f16(const u32x4_t& v, float (&z)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    f16x2_t h;
+    __builtin_memcpy(&h, &w[k], 4);
+    z[2 * k] = float(h.x);
+    z[2 * k + 1] = float(h.y);
+  }
+}
+
+// One 16-byte vector of stored logits -> floats (8 for the 2-byte types, 4 for fp32) and back.
+template <int DT> __device__ __forceinline__ void unpack_vec(const u32x4_t& v, float (&z)[Storage<DT>::kPerVec]) {
+  if constexpr (DT == kBF16) unpack8(v, z);
+  else if constexpr (DT == kF16) unpack8_f16(v, z);
+  else {
+    z[0] = __uint_as_float(v.x); z[1] = __uint_as_float(v.y);
+    z[2] = __uint_as_float(v.z); z[3] = __uint_as_float(v.w);
+  }
+}
+template <int DT> __device__ __forceinline__ u32x4_t pack_vec(const float (&d)[Storage<DT>::kPerVec]) {
+  u32x4_t o;
+  if constexpr (DT == kBF16) {
+    o.x = pack_bf16x2(d[0], d[1]); o.y = pack_bf16x2(d[2], d[3]);
+    o.z = pack_bf16x2(d[4], d[5]); o.w = pack_bf16x2(d[6], d[7]);
+  } else if constexpr (DT == kF16) {
+    o.x = pack_f16x2(d[0], d[1]); o.y = pack_f16x2(d[2], d[3]);
+    o.z = pack_f16x2(d[4], d[5]); o.w = pack_f16x2(d[6], d[7]);
+  } else {
+    o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
+    o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
+  }
+  return o;
 }
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_signal_mask(
 // ---------------------------------------------------------------- token terms
 // LP_GIVEN: the current log-prob is read from `logprob_in` (fused LM-head path) instead of
 // being formed as z[t, y] - lse[t].
-template <bool BF16, bool LP_GIVEN>
+template <int DT, bool LP_GIVEN>
 __global__ __launch_bounds__(256) void k_token_terms(
     const void* __restrict__ logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ lse, const float* __restrict__ logprob_in,
@@ -103,10 +103,7 @@ __global__ __launch_bounds__(256) void k_token_terms(
       if constexpr (LP_GIVEN) {
         lp = logprob_in[t];
       } else {
-        float zy;
-        if constexpr (BF16) zy = bf16_to_f32(reinterpret_cast<const uint16_t*>(logits)[size_t(t) * size_t(ld) + y]);
-        else zy = reinterpret_cast<const float*>(logits)[size_t(t) * size_t(ld) + y];
-        lp = zy - lse[t];
+        lp = load_elt<DT>(logits, int64_t(t) * ld + y) - lse[t];
       }
       if (A != 0.f) {
         const float rho = expf(lp - old_logprob[t]);
@@ -176,8 +173,29 @@ __global__ __launch_bounds__(kReduceNT) void k_loss_reduce(
 }
 
 // ---------------------------------------------------------------- dlogits
+// dz_j = s(z_j) * exp(z_j - lse) (+ g at the sampled token), s = -g, or a z_j + b with the entropy term.
+template <bool ENT>
+__device__ __forceinline__ float grad_elt(float z, float a, float b, float c) {
+  return (ENT ? fmaf(a, z, b) : b) * exp2_fast(fmaf(z, kLog2e, c));
+}
+
+// One 16-byte vector of logits -> one of gradient; k = index of the vector in its row.
+template <int DT, bool ENT>
+__device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, float g, float a, float b, float c) {
+  constexpr int E = Storage<DT>::kPerVec;
+  float z[E], d[E];
+  unpack_vec<DT>(v, z);
+#pragma unroll
+  for (int e = 0; e < E; ++e) d[e] = grad_elt<ENT>(z[e], a, b, c);
+  if (k == y / E) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) d[e] += (e == y % E) ? g : 0.f;
+  }
+  return pack_vec<DT>(d);
+}
+
 // ENT: the row also carries the entropy-bonus term, dz_j = pi_j (a z_j + b) + g 1[j = y].
-template <int NT, bool BF16, bool VEC, bool ENT>
+template <int NT, int DT, bool VEC, bool ENT>
 __global__ __launch_bounds__(NT) void k_dlogits(
     const void* logits, int64_t T, int V, int64_t ld, const int32_t* __restrict__ targets,
     const float* __restrict__ lse, const float* __restrict__ g_arr, const float* __restrict__ ea,
@@ -186,8 +204,8 @@ __global__ __launch_bounds__(NT) void k_dlogits(
   const float g = g_arr[t];
   float a = 0.f;
   if constexpr (ENT) a = ea[t];
-  constexpr size_t kEltBytes = BF16 ? 2 : 4;
-  constexpr int E = BF16 ? 8 : 4;
+  constexpr size_t kEltBytes = Storage<DT>::kBytes;
+  constexpr int E = Storage<DT>::kPerVec;
   const size_t row_off = size_t(t) * size_t(ld) * kEltBytes;
   const char* zrow = reinterpret_cast<const char*>(logits) + row_off;
   char* drow = reinterpret_cast<char*>(dlogits) + row_off;
@@ -200,95 +218,43 @@ __global__ __launch_bounds__(NT) void k_dlogits(
       const u32x4_t zero = {0u, 0u, 0u, 0u};
       for (int i = tid; i < nvec; i += NT) __builtin_nontemporal_store(zero, dv + i);
       const int j = nvec * E + tid;
-      if (j < V) {
-        if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
-        else reinterpret_cast<float*>(drow)[j] = 0.f;
-      }
+      if (j < V) store_elt<DT>(drow, j, 0.f);
     } else {
-      for (int j = tid; j < V; j += NT) {
-        if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
-        else reinterpret_cast<float*>(drow)[j] = 0.f;
-      }
+      for (int j = tid; j < V; j += NT) store_elt<DT>(drow, j, 0.f);
     }
     return;
   }
 
   const int y = targets[t];
   const float c = -lse[t] * kLog2e;
-  const float ng = -g;
-  float b = ng;
+  float b = -g;
   if constexpr (ENT) b = eb[t];
-  // dz_j = -g * exp(z_j - lse) (+ g at the sampled token); with the entropy term (a z_j + b) replaces -g
-  auto scale = [&](float z) -> float { return ENT ? fmaf(a, z, b) : ng; };
   auto grad = [&](float z, int j) -> float {
-    float d = scale(z) * exp2_fast(fmaf(z, kLog2e, c));
+    const float d = grad_elt<ENT>(z, a, b, c);
     return j == y ? d + g : d;
   };
   if constexpr (VEC) {
     const u32x4_t* zv = reinterpret_cast<const u32x4_t*>(zrow);
     u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
     const int nvec = V / E;
-    const int yvec = y / E;
     constexpr int UNROLL = 4;
-    auto one = [&](const u32x4_t& v, int i) -> u32x4_t {
-      u32x4_t o;
-      if constexpr (BF16) {
-        float z[8];
-        unpack8(v, z);
-        float d[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) d[k] = scale(z[k]) * exp2_fast(fmaf(z[k], kLog2e, c));
-        if (i == yvec) {
-#pragma unroll
-          for (int k = 0; k < 8; ++k) d[k] += (k == (y & 7)) ? g : 0.f;
-        }
-        o.x = pack_bf16x2(d[0], d[1]);
-        o.y = pack_bf16x2(d[2], d[3]);
-        o.z = pack_bf16x2(d[4], d[5]);
-        o.w = pack_bf16x2(d[6], d[7]);
-      } else {
-        float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) d[k] = scale(d[k]) * exp2_fast(fmaf(d[k], kLog2e, c));
-        if (i == yvec) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) d[k] += (k == (y & 3)) ? g : 0.f;
-        }
-        o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
-        o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
-      }
-      return o;
-    };
     int i = tid;
     for (; i + (UNROLL - 1) * NT < nvec; i += UNROLL * NT) {
       u32x4_t v[UNROLL];
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(zv + i + u * NT);
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u) __builtin_nontemporal_store(one(v[u], i + u * NT), dv + i + u * NT);
+      for (int u = 0; u < UNROLL; ++u)
+        __builtin_nontemporal_store(dlogits_vec<DT, ENT>(v[u], i + u * NT, y, g, a, b, c), dv + i + u * NT);
     }
     for (; i < nvec; i += NT) {
       u32x4_t v = __builtin_nontemporal_load(zv + i);
-      __builtin_nontemporal_store(one(v, i), dv + i);
+      __builtin_nontemporal_store(dlogits_vec<DT, ENT>(v, i, y, g, a, b, c), dv + i);
     }
     const int j = nvec * E + tid;
-    if (j < V) {
-      if constexpr (BF16) {
-        const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
-        reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(grad(z, j));
-      } else {
-        reinterpret_cast<float*>(drow)[j] = grad(reinterpret_cast<const float*>(zrow)[j], j);
-      }
-    }
+    if (j < V) store_elt<DT>(drow, j, grad(load_elt<DT>(zrow, j), j));
   } else {
-    for (int j = tid; j < V; j += NT) {
-      if constexpr (BF16) {
-        const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
-        reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(grad(z, j));
-      } else {
-        reinterpret_cast<float*>(drow)[j] = grad(reinterpret_cast<const float*>(zrow)[j], j);
-      }
-    }
+    for (int j = tid; j < V; j += NT) store_elt<DT>(drow, j, grad(load_elt<DT>(zrow, j), j));
   }
 }
 
@@ -302,44 +268,13 @@ constexpr int kSegNT = 256;
 constexpr int kSegVPT = 1;
 constexpr int kSegVecs = kSegNT * kSegVPT;   // vectors per segment
 
-template <bool BF16, bool ENT>
-__device__ __forceinline__ u32x4_t dlogits_vec(const u32x4_t& v, int k, int y, float g, float a, float b, float c) {
-  auto scale = [&](float z) -> float { return ENT ? fmaf(a, z, b) : b; };   // b = -g without the entropy term
-  u32x4_t o;
-  if constexpr (BF16) {
-    float z[8], d[8];
-    unpack8(v, z);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) d[e] = scale(z[e]) * exp2_fast(fmaf(z[e], kLog2e, c));
-    if (k == (y >> 3)) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) d[e] += (e == (y & 7)) ? g : 0.f;
-    }
-    o.x = pack_bf16x2(d[0], d[1]);
-    o.y = pack_bf16x2(d[2], d[3]);
-    o.z = pack_bf16x2(d[4], d[5]);
-    o.w = pack_bf16x2(d[6], d[7]);
-  } else {
-    float d[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) d[e] = scale(d[e]) * exp2_fast(fmaf(d[e], kLog2e, c));
-    if (k == (y >> 2)) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) d[e] += (e == (y & 3)) ? g : 0.f;
-    }
-    o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
-    o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);
-  }
-  return o;
-}
-
-template <bool BF16, bool ENT>
+template <int DT, bool ENT>
 __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
     const void* logits, int V, int64_t ld, int segs, const int32_t* __restrict__ targets,
     const float* __restrict__ lse, const float* __restrict__ g_arr, const float* __restrict__ ea,
     const float* __restrict__ eb, void* dlogits) {
-  constexpr int E = BF16 ? 8 : 4;
-  constexpr size_t kEltBytes = BF16 ? 2 : 4;
+  constexpr int E = Storage<DT>::kPerVec;
+  constexpr size_t kEltBytes = Storage<DT>::kBytes;
   const int64_t t = blockIdx.x / segs;
   const int seg = blockIdx.x % segs;
   const float g = g_arr[t];
@@ -356,10 +291,7 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
 #pragma unroll
     for (int i = 0; i < kSegVPT; ++i)
       if (k0 + i * kSegNT < nvec) reinterpret_cast<u32x4_t*>(drow)[k0 + i * kSegNT] = u32x4_t{0u, 0u, 0u, 0u};
-    if (tail) {
-      if constexpr (BF16) reinterpret_cast<uint16_t*>(drow)[j] = 0;
-      else reinterpret_cast<float*>(drow)[j] = 0.f;
-    }
+    if (tail) store_elt<DT>(drow, j, 0.f);
     return;
   }
   u32x4_t v[kSegVPT];
@@ -373,45 +305,37 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
 #pragma unroll
   for (int i = 0; i < kSegVPT; ++i) {
     const int k = k0 + i * kSegNT;
-    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = dlogits_vec<BF16, ENT>(v[i], k, y, g, a, b, c);
+    if (k < nvec) reinterpret_cast<u32x4_t*>(drow)[k] = dlogits_vec<DT, ENT>(v[i], k, y, g, a, b, c);
   }
   if (tail) {
-    if constexpr (BF16) {
-      const float z = bf16_to_f32(reinterpret_cast<const uint16_t*>(zrow)[j]);
-      float d = (ENT ? fmaf(a, z, b) : b) * exp2_fast(fmaf(z, kLog2e, c));
-      if (j == y) d += g;
-      reinterpret_cast<uint16_t*>(drow)[j] = f32_to_bf16(d);
-    } else {
-      const float z = reinterpret_cast<const float*>(zrow)[j];
-      float d = (ENT ? fmaf(a, z, b) : b) * exp2_fast(fmaf(z, kLog2e, c));
-      if (j == y) d += g;
-      reinterpret_cast<float*>(drow)[j] = d;
-    }
+    float d = grad_elt<ENT>(load_elt<DT>(zrow, j), a, b, c);
+    if (j == y) d += g;
+    store_elt<DT>(drow, j, d);
   }
 }
 
-template <bool BF16, bool VEC, bool ENT>
+template <int DT, bool VEC, bool ENT>
 static void dispatch_dlogits(const void* logits, int64_t T, int V, int64_t ld, const int32_t* targets,
                              const float* lse, const float* g, const float* ea, const float* eb, void* dlogits,
                              hipStream_t s) {
-  const int per_vec = VEC ? (BF16 ? 8 : 4) : 1;
+  const int per_vec = VEC ? Storage<DT>::kPerVec : 1;
   const int64_t work = (V + per_vec - 1) / per_vec;
   if constexpr (VEC) {
     const int64_t segs = (V / per_vec + kSegVecs - 1) / kSegVecs;
     if (work > 16 * 256 && T * segs < (int64_t(1) << 31)) {
-      hipLaunchKernelGGL((k_dlogits_seg<BF16, ENT>), dim3(unsigned(T * segs)), dim3(kSegNT), 0, s, logits, V, ld,
+      hipLaunchKernelGGL((k_dlogits_seg<DT, ENT>), dim3(unsigned(T * segs)), dim3(kSegNT), 0, s, logits, V, ld,
                          int(segs), targets, lse, g, ea, eb, dlogits);
       return;
     }
   }
   if (work <= 4 * 64)
-    hipLaunchKernelGGL((k_dlogits<64, BF16, VEC, ENT>), dim3((unsigned)T), dim3(64), 0, s, logits, T, V, ld, targets,
+    hipLaunchKernelGGL((k_dlogits<64, DT, VEC, ENT>), dim3((unsigned)T), dim3(64), 0, s, logits, T, V, ld, targets,
                        lse, g, ea, eb, dlogits);
   else if (work <= 16 * 256)
-    hipLaunchKernelGGL((k_dlogits<256, BF16, VEC, ENT>), dim3((unsigned)T), dim3(256), 0, s, logits, T, V, ld, targets,
+    hipLaunchKernelGGL((k_dlogits<256, DT, VEC, ENT>), dim3((unsigned)T), dim3(256), 0, s, logits, T, V, ld, targets,
                        lse, g, ea, eb, dlogits);
   else
-    hipLaunchKernelGGL((k_dlogits<512, BF16, VEC, ENT>), dim3((unsigned)T), dim3(512), 0, s, logits, T, V, ld, targets,
+    hipLaunchKernelGGL((k_dlogits<512, DT, VEC, ENT>), dim3((unsigned)T), dim3(512), 0, s, logits, T, V, ld, targets,
                        lse, g, ea, eb, dlogits);
 }
 
@@ -420,11 +344,14 @@ static void dispatch_dlogits_dtype(int32_t dtype, bool vec, const void* logits, 
                                    const int32_t* targets, const float* lse, const float* g, const float* ea,
                                    const float* eb, void* dlogits, hipStream_t s) {
   if (dtype == AERO_BF16) {
-    if (vec) dispatch_dlogits<true, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
-    else dispatch_dlogits<true, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    if (vec) dispatch_dlogits<kBF16, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<kBF16, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+  } else if (dtype == AERO_F16) {
+    if (vec) dispatch_dlogits<kF16, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<kF16, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
   } else {
-    if (vec) dispatch_dlogits<false, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
-    else dispatch_dlogits<false, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    if (vec) dispatch_dlogits<kF32, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<kF32, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
   }
 }
 
@@ -437,7 +364,7 @@ aero_status token_terms_from_logprob(int64_t T, int V, const int32_t* targets, c
                                      float* eb, float* loss, float* clip_frac, int32_t* err_flag, hipStream_t s) {
   const unsigned blocks = unsigned((T + 255) / 256);
   if (T > 0)
-    hipLaunchKernelGGL((k_token_terms<true, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
+    hipLaunchKernelGGL((k_token_terms<kBF16, true>), dim3(blocks), dim3(256), 0, s, nullptr, T, V, int64_t(0),
                        targets, lse, logprob, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
                        grad_scale, ent_coef, entropy, kl_coef, ref_logprob, g, term, flag, ea, eb, nullptr, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, term, flag, T, loss, clip_frac);
@@ -457,7 +384,7 @@ static aero_status loss_bwd_run(
   if (kl_coef != 0.f && T > 0 && !ref_logprob) return AERO_ERR_NULL;
   if (lse && ent && !entropy) return AERO_ERR_NULL;             // H_t must come with the given lse
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
-  if (dtype != AERO_BF16 && dtype != AERO_F32) return AERO_ERR_DTYPE;
+  if (dtype != AERO_BF16 && dtype != AERO_F32 && dtype != AERO_F16) return AERO_ERR_DTYPE;
   if (!loss) return AERO_ERR_NULL;
   hipStream_t s = as_stream(stream);
   if (T > 0 && (!logits || !targets || !old_logprob || !token_rollout || !adv || !weight)) return AERO_ERR_NULL;
@@ -499,19 +426,15 @@ static aero_status loss_bwd_run(
   } else if (entropy_out || lse_out) {
     return AERO_ERR_NULL;   // these outputs exist only when the statistics are computed here
   }
-  if (dtype == AERO_BF16)
-    hipLaunchKernelGGL((k_token_terms<true, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
-                       lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr,
-                       ent ? ws.eb : nullptr, lp_dst, err_flag);
-  else
-    hipLaunchKernelGGL((k_token_terms<false, false>), dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets,
-                       lse, nullptr, old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale,
-                       entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag, ent ? ws.ea : nullptr,
-                       ent ? ws.eb : nullptr, lp_dst, err_flag);
+  auto token_terms = dtype == AERO_BF16 ? k_token_terms<kBF16, false>
+                     : dtype == AERO_F16 ? k_token_terms<kF16, false> : k_token_terms<kF32, false>;
+  hipLaunchKernelGGL(token_terms, dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets, lse,
+                     static_cast<const float*>(nullptr), old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
+                     grad_scale, entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag,
+                     ent ? ws.ea : nullptr, ent ? ws.eb : nullptr, lp_dst, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
   if (dlogits) {
-    const size_t elt = dtype == AERO_BF16 ? 2 : 4;
+    const size_t elt = dtype == AERO_F32 ? 4 : 2;
     const bool vec = reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0 &&
                      (size_t(ld) * elt) % 16 == 0;
     if (ent) dispatch_dlogits_dtype<true>(dtype, vec, logits, T, V, ld, targets, lse, ws.g, ws.ea, ws.eb, dlogits, s);

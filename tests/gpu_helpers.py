@@ -14,14 +14,14 @@ def dev(x):
 
 
 def logits_to_dev(arr, dtype):
-    """Host logits (float32 values or bf16 bit patterns in uint16) -> device tensor."""
-    if dtype == "bf16":
-        return torch.from_numpy(arr.view(np.int16)).to(DEV).view(torch.bfloat16)
+    """Host logits (float32 values, or bf16 / fp16 bit patterns in uint16) -> device tensor."""
+    if dtype in ("bf16", "f16"):
+        return torch.from_numpy(arr.view(np.int16)).to(DEV).view(torch.bfloat16 if dtype == "bf16" else torch.float16)
     return torch.from_numpy(arr).to(DEV)
 
 
 def to_np64(t):
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.float().cpu().numpy().astype(np.float64)
     return t.cpu().numpy().astype(np.float64)
 

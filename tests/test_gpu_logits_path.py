@@ -145,6 +145,19 @@ def test_fwd_f32_shapes(gh, V, ld):
     assert check_fwd(gh, wl) == 0
 
 
+# fp16 storage (beyond the paper's bf16 runs, App. C): same definitions on binary16 values, the
+# checker widens them exactly.  "Parity unpinned" by the paper in the sense that no experiment of
+# it uses this format; the arithmetic is the pinned one.
+@pytest.mark.parametrize("V,ld", [(1000, 1000), (4999, 5008), (151936, 151936), (65, 72), (7, 8)])
+def test_fwd_f16_shapes(gh, V, ld):
+    slots = 4 if V > 100000 else 12
+    wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots, dtype="f16")
+    active = (wl.token_rollout >= 0).astype(np.uint8)
+    assert check_fwd(gh, wl) == 0
+    assert check_fwd(gh, wl, row_active=active) == 0
+    assert check_fwd(gh, wl, offset_elems=3) == 0          # misaligned base: scalar path
+
+
 def test_fwd_misaligned_base_and_bad_targets(gh):
     wl = ai.make_config("cfg2", V=4096, slots=6, len_lo=1, len_hi=6)
     assert check_fwd(gh, wl, offset_elems=3) == 0
@@ -190,7 +203,10 @@ def test_fwd_empty(gh):
 # ------------------------------------------------------------------ loss and dlogits
 
 def elt_rounding(dtype, ref_abs):
-    """One rounding of the stored gradient entry: bf16 has 8 significant bits, fp32 24."""
+    """One rounding of the stored gradient entry: bf16 has 8 significant bits, fp32 24, fp16 11
+    and a fixed grid of 2^-24 below 2^-14 (subnormals)."""
+    if dtype == "f16":
+        return ref_abs * 2.0 ** -11 + 2.0 ** -25
     return ref_abs * (2.0 ** -8 if dtype == "bf16" else 2.0 ** -23) + 1e-30
 
 
@@ -237,14 +253,14 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     dz = gh.to_np64(out["dlogits"])[:, :wl.V]
     want = ref["dlogits"]
     assert np.isfinite(dz).all()
-    assert np.abs(dz - want).max() <= DZ_ATOL
+    assert np.abs(dz - want).max() <= DZ_ATOL * max(1.0, grad_scale)    # stated for the unscaled gradient
     # scale of a row: |g_t| for the surrogate, |e_t| (|p ln p| + p H_t) <= |e_t| (1 + H_t) for the entropy term
     scale = np.abs(ref["g"]) + np.abs(ref["e"]) * (1.0 + ent_ref)
     bound = 1e-2 * scale[:, None] + elt_rounding(wl.dtype, np.abs(want))
     assert (np.abs(dz - want) <= bound).all()
     dead = (ref["g"] == 0) & (ref["e"] == 0)
     raw = out["dlogits"][:, :wl.V]
-    bits = raw.view(torch.int16) if wl.dtype == "bf16" else raw.view(torch.int32)
+    bits = raw.view(torch.int16) if wl.dtype in ("bf16", "f16") else raw.view(torch.int32)
     assert not bits[torch.from_numpy(dead).to(gh.DEV)].any()       # exactly +0, sign bit included
     if wl.ld > wl.V and not inplace:                                # pad columns are not written
         assert (out["dlogits"][:, wl.V:].float() == 7.0).all()
@@ -328,6 +344,21 @@ def test_loss_bwd_cfg2_reduced(gh, V, ld, slots):
     check_loss_bwd(gh, wl, dict(), sigma_old=0.3, use_oracle_lse=False, stats=True)
     check_loss_bwd(gh, wl, dict(), inplace=True)
     check_loss_bwd(gh, wl, dict(), inplace=True, use_oracle_lse=False, stats=True, grad_scale=3.0)
+
+
+@pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10), (32768, 32768, 8)])
+def test_loss_bwd_f16(gh, V, ld, slots):
+    """fp16 logits and gradients.  grad_scale lifts the gradient entries out of fp16's subnormal
+    range, as a caller training in fp16 would; the unscaled run checks the rounding to that grid."""
+    def wl():
+        return ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots, dtype="f16")
+    check_loss_bwd(gh, wl(), dict(), grad_scale=4096.0)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, expect_clip=True, grad_scale=4096.0, stats=True)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, inplace=True, grad_scale=4096.0)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3)
+    check_loss_bwd(gh, wl(), dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=False,
+                   entropy_coef=1e-3, kl_coef=0.04, grad_scale=4096.0)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, adv_map=lambda a: np.abs(a) + np.float32(0.25), strict_loss=True)
 
 
 def test_loss_bwd_cfg3_reduced(gh):
@@ -482,7 +513,7 @@ def test_host_side_argument_errors(gh):
     with pytest.raises(aero.AeroError, match="NULL"):
         aero.aero_logprob_fwd(z, 4, 16, 16, None, None, f, f, f)
     with pytest.raises(aero.AeroError, match="unsupported dtype"):
-        aero.aero_logprob_fwd(z.to(torch.float16), 4, 16, 16, t, None, f, f, f)
+        aero.aero_logprob_fwd(z.to(torch.float64), 4, 16, 16, t, None, f, f, f)
     with pytest.raises(aero.AeroError, match="workspace"):
         aero.aero_grpo_loss_bwd(z, 4, 16, 16, t, None, f, t, f, f, 4, 0.2, 0.2, 1.0, f[:1], None, None, None,
                                 torch.zeros(8, dtype=torch.uint8, device=gh.DEV))

@@ -53,6 +53,24 @@ def test_bf16_roundtrip_matches_torch():
     assert np.array_equal(orc.widen(bits, "bf16"), tb.double().numpy())
 
 
+def test_f16_roundtrip_matches_torch():
+    """binary16 storage: the generator's rounding and the checker's widening against torch's
+    conversions, bit for bit (ties, subnormals, the largest finite value, every bit pattern)."""
+    rng = np.random.default_rng(1)
+    x = (rng.standard_normal(100000) * 3).astype(np.float32)
+    x[:8] = [0.0, -0.0, 1.0, 1.00048828125, 1.00146484375, 65504.0, 5.9604645e-8, 3.0e-8]
+    bits = ai.f32_to_f16_bits(x)
+    th = torch.from_numpy(x).to(torch.float16)
+    assert np.array_equal(bits, th.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(orc.widen(bits, "f16"), th.double().numpy())
+    every = np.arange(65536, dtype=np.uint16)
+    finite = (every & 0x7C00) != 0x7C00
+    want = torch.from_numpy(every.view(np.int16)).view(torch.float16).double().numpy()
+    assert np.array_equal(orc.widen(every, "f16")[finite], want[finite])
+    assert orc.widen(np.array([0x3C00, 0xC000, 0x0001, 0x7BFF], np.uint16), "f16").tolist() == \
+        [1.0, -2.0, 2.0 ** -24, 65504.0]
+
+
 # ------------------------------------------------------------------ group statistics
 
 @pytest.mark.parametrize("n", range(2, 17))
