@@ -20,13 +20,38 @@ def gh():
 
 @pytest.mark.parametrize("mode", ["grpo", "aero", "aero+terms"])
 def test_step_matches_checker(gh, mode):
-    import paper_2602_14338_amd as aero
-    from paper_2602_14338_amd import step
-    V, mb_tokens = 512, 96
     groups = ai.make_step_groups(seed=11, Q=10, N=8, len_lo=3, len_hi=40, zero_var_frac=0.35)
     params = dict(reject_enable=1, posterior_mode=1) if mode != "grpo" else dict()
     # "+terms": the entropy bonus (Table 8) and Eq. 2's KL penalty ride along on every micro-batch
     ent_coef, kl_coef = (0.01, 0.05) if mode == "aero+terms" else (0.0, 0.0)
+    step_against_checker(gh, groups, params, ent_coef, kl_coef, expect_dropped=mode != "grpo")
+
+
+def test_allocated_step_matches_checker(gh):
+    """The whole mechanism joined up: the two-stage allocation loop (Sec. 4.1, Alg. 1: exploration,
+    rescue with the App. C budget caps) decides the ragged groups over a rollout simulator, the
+    curation call applies Strategies 2 and 3 to them, the kept rollouts are packed into
+    micro-batches, and the summed loss and every gradient row match the checker on the same groups."""
+    from types import SimpleNamespace
+    from paper_2602_14338_amd.controller import allocate_rollouts
+    P = 14
+    sim = ai.RolloutSimulator(33, P, beta=0.4, len_lo=3, len_hi=30)
+    alloc = allocate_rollouts(sim.draw, P)
+    assert (alloc.rescued_at > 0).any() and (alloc.n > 8).any() and alloc.generated <= 16 * P
+    keys = np.random.default_rng(33).integers(0, 2 ** 32, size=alloc.rewards.size, dtype=np.uint32)
+    groups = SimpleNamespace(rewards=alloc.rewards, lengths=alloc.lengths, group_offsets=alloc.group_offsets,
+                             keep_priority=keys, R=int(alloc.rewards.size), Q=P, seed=33)
+    ga = step_against_checker(gh, groups, dict(reject_enable=1, posterior_mode=1), 0.0, 0.0, expect_dropped=True)
+    kept = np.diff(ga["kept_offsets"])
+    rescued = alloc.rescued_at > 0
+    assert np.array_equal(kept[rescued], 2 * alloc.c[rescued])      # rescued queries train on balanced pairs
+    assert kept.mean() < alloc.n.mean()
+
+
+def step_against_checker(gh, groups, params, ent_coef, kl_coef, expect_dropped):
+    import paper_2602_14338_amd as aero
+    from paper_2602_14338_amd import step
+    V, mb_tokens = 512, 96
     ga = orc.group_advantage(groups.rewards, groups.lengths, groups.group_offsets, groups.keep_priority,
                              OracleParams(**params))
     cur = step.curate(gh.dev(groups.rewards), gh.dev(groups.lengths), gh.dev(groups.group_offsets),
@@ -34,7 +59,7 @@ def test_step_matches_checker(gh, mode):
     torch.cuda.synchronize()
     keep = cur.keep_mask.cpu().numpy()
     assert np.array_equal(keep, ga["keep_mask"]) and int(cur.err.item()) == 0
-    if mode != "grpo":
+    if expect_dropped:
         assert keep.sum() < groups.R          # something was dropped and is never packed
     rollouts = np.nonzero(keep)[0]
     plan = step.plan_microbatches(groups.lengths, rollouts, mb_tokens)
@@ -71,6 +96,7 @@ def test_step_matches_checker(gh, mode):
     bound = 1e-2 * scale[:, None] + np.abs(ref["dlogits"]) * 2.0 ** -23 + 1e-30
     assert (np.abs(got - ref["dlogits"]) <= bound).all()
     assert not got[(ref["g"] == 0) & (ref["e"] == 0)].any()
+    return ga
 
 
 @pytest.mark.parametrize("S", [0, 2])
