@@ -63,8 +63,27 @@ __device__ __forceinline__ void tile_of_index(int npid, int tiles_m, int tiles_n
   tn = within / gm;
 }
 
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
-  const int npid = xcd_regroup(blockIdx.x, gridDim.x);
+// The same regrouping in whole columns of a band: the n positions of a launch are cut into units
+// of 8 consecutive positions (one column of 8 tile rows), every XCD gets a contiguous run of
+// whole units (run lengths differ by at most one unit), so that the workgroups resident on an
+// XCD always cover whole columns, whatever n is.  The launch grid is xcd_grid(n) >= n workgroups;
+// the surplus ones get -1 and leave.
+inline int xcd_grid(int n) { return 64 * (((n + 7) / 8 + 7) / 8); }
+__device__ __forceinline__ int xcd_position(int pid, int n) {
+  const int units = (n + 7) / 8, q = units / 8, r = units % 8;
+  const int xcd = pid % 8, local = pid / 8;
+  const int ul = local / 8;
+  if (ul >= q + (xcd < r ? 1 : 0)) return -1;
+  const int pos = (xcd * q + min(xcd, r) + ul) * 8 + local % 8;
+  return pos < n ? pos : -1;
+}
+
+// tile0: position in the tile order of this launch's first tile, n: tiles of this launch (a
+// kernel's tiles may be spread over several launches).  False: a surplus workgroup.
+__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int tile0, int n, int& tm, int& tn) {
+  const int pos = xcd_position(blockIdx.x, n);
+  if (pos < 0) return false;
+  const int npid = tile0 + pos;
   constexpr int GM = 8;
   const int group_sz = GM * tiles_n;
   const int first_m = (npid / group_sz) * GM;
@@ -72,6 +91,7 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
   const int within = npid % group_sz;
   tm = first_m + within % gm;
   tn = within / gm;
+  return true;
 }
 
 struct Frags {

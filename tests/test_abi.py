@@ -46,7 +46,7 @@ def test_status_strings_and_workspace_sizes_on_host():
     assert a % 256 == 0 and 16384 * 4 * 5 <= a <= 16384 * 4 * 10
     f4 = aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=16384, V=151936, H=1536)
     f5 = aero.aero_workspace_bytes(binding.OP_LMHEAD_FUSED, T=32768, V=152064, H=3584)
-    assert 0 < f4 < 6 << 30 and f4 < f5 < 8 << 30
+    assert 0 < f4 < 16 << 30 and f4 < f5 < 32 << 30      # both layouts of the bf16 dz are held whole
 
 
 def test_binding_has_no_cpu_fallback():
