@@ -21,7 +21,7 @@ constexpr int kTile = 256;          // tile edge in both output dimensions
 constexpr int kGemmNT = 512;        // threads per workgroup (8 waves)
 constexpr int kMB = 4, kNB = 2;     // 32 x 32 blocks per wave: 128 rows x 64 columns
 constexpr size_t kGemmStageBytes = 131072;  // two stages of (256 + 256) x 64 bf16
-constexpr size_t kWarmSinkOff = 135168;     // past the largest epilogue staging area (256 x 264 bf16)
+constexpr size_t kWarmSinkOff = 135168;     // past the stages (128 KB) and the largest epilogue staging area (256 x 256 bf16)
 constexpr size_t kGemmLdsBytes = kWarmSinkOff + 2048;   // + a 256-byte sink per wave for the warm-up loads
 
 // Position of an accumulator element inside the 256 x 256 tile.

@@ -184,17 +184,19 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint16_t* __restrict_
 // ------------------------------------------------------------------------------------------
 // forward: per-tile softmax partials
 // ------------------------------------------------------------------------------------------
-// grid: tiles_v * tiles_t workgroups.  Hf holds the compacted rows ([T_pad][H], zero past the
-// count); part_* are [tiles_v][T_pad], indexed by compact row.
+// grid: xcd_grid(tiles_v * T_pad / 256) workgroups.  Hf holds the compacted rows ([T_pad][H], zero
+// past the count); part_* are [tiles_v][T_pad], indexed by compact row.
 __global__ __launch_bounds__(kGemmNT, 2) void k_fused_stats(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hf, int V, int H, int tiles_v, int tiles_t,
-    int tile0, int n_tiles, int64_t T_pad, const int32_t* __restrict__ nf, float* __restrict__ part_m,
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hf, int V, int H, int tiles_v,
+    int64_t T_pad, const int32_t* __restrict__ nf, float* __restrict__ part_m,
     float* __restrict__ part_s, float* __restrict__ part_sz) {
   extern __shared__ __align__(16) uint16_t smem[];
+  // the tile order covers only the token tiles that hold rows with a target (count known on the
+  // device), so that every XCD gets the same number of real tiles; the rest of the grid leaves
+  const int tiles_t_act = nf[1] / kTile;
   int tv, tt;
-  if (!tile_of_block(tiles_v, tiles_t, tile0, n_tiles, tv, tt)) return;
+  if (!tile_of_block(tiles_v, tiles_t_act, 0, tiles_v * tiles_t_act, tv, tt)) return;
   const int m0 = tv * kTile, n0 = tt * kTile;
-  if (n0 >= nf[1]) return;   // beyond the rows with a target: uniform exit
   Acc acc;
   gemm_tile_auto(W, H, V, Hf, H, int(T_pad), H, m0, n0, smem, acc);
 
@@ -448,15 +450,16 @@ __global__ __launch_bounds__(256) void k_gather_transpose_vec(
 template <bool ENT>
 __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hc, int V, int H,
-    int tiles_v, int tiles_t, int tile0, int n_tiles, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
+    int tiles_v, int64_t T_pad, int VC, const int32_t* __restrict__ nact,
     const float* __restrict__ gc, const float* __restrict__ lsec, const int32_t* __restrict__ yc,
     const float* __restrict__ ac, const float* __restrict__ bc, uint16_t* __restrict__ dz,
     uint16_t* __restrict__ dzT) {
   extern __shared__ __align__(16) uint16_t smem[];
+  // tile order over the active token tiles only (see k_fused_stats)
+  const int tiles_t_act = nact[1] / kTile;
   int tv, tt;
-  if (!tile_of_block(tiles_v, tiles_t, tile0, n_tiles, tv, tt)) return;
+  if (!tile_of_block(tiles_v, tiles_t_act, 0, tiles_v * tiles_t_act, tv, tt)) return;
   const int m0 = tv * kTile, n0 = tt * kTile;
-  if (n0 >= nact[1]) return;   // beyond the active tokens: uniform exit
   Acc acc;
   gemm_tile_auto(W, H, V, Hc, H, int(T_pad), H, m0, n0, smem, acc);
 
@@ -507,9 +510,23 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
         }
     }
   }
-  // The tile leaves through LDS so that both layouts are written with 16-byte coalesced
-  // stores.  Rows are padded by 8 elements to spread the banks.
-  constexpr int kPitch = kTile + 8;
+  // The tile leaves through LDS so that both layouts are written with 16-byte coalesced stores.
+  // Both LDS images are 256 rows of 512 bytes without padding; a row starts at bank 0, so the
+  // positions inside a row are XOR-swizzled with bits of the row index, chosen so that the lanes
+  // of every LDS instruction below fall on distinct banks (64 banks of 4 bytes):
+  //   image 1, L1[token][vocab]: the 16-byte chunk c = vocab / 8 sits at chunk position
+  //     c ^ g(token) (low four bits), g = ((token & 1) << 3) | ((token >> 1) & 7), and the two
+  //     8-byte halves of a chunk are exchanged when token & 16.  Writes: 32 lanes = 32 consecutive
+  //     tokens, 8 bytes each, one vocabulary position -> 32 distinct bank pairs.  Reads: 16 lanes =
+  //     2 tokens x 8 chunks -> the two tokens use different halves of the banks.
+  //   image 2, L2[vocab][token]: bits 4-5 of the 4-byte word index are XORed with
+  //     s(vocab) = ((vocab & 1) << 1) | ((vocab >> 2) & 1).  Writes: 64 lanes = rows (r, r + 1,
+  //     r + 4, r + 5) x 16 consecutive words -> four distinct groups of 16 banks.  Reads: 16 lanes
+  //     = 2 rows x 8 chunks, the rows in different halves of the banks.
+  auto l1_chunk = [](int tok, int c) -> int {
+    const int g = ((tok & 1) << 3) | ((tok >> 1) & 7);
+    return (c & ~15) | ((c ^ g) & 15);
+  };
   // ---- [token][vocab] ----
 #pragma unroll
   for (int nb = 0; nb < kNB; ++nb) {
@@ -518,9 +535,10 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int row0 = acc_row(wm, mb, i4 * 4, lane);
+        const int row0 = acc_row(wm, mb, i4 * 4, lane);   // a multiple of 4
+        const int half = ((row0 >> 2) ^ (tcol >> 4)) & 1;
         uint2 two = {pk[nb][mb][i4][0], pk[nb][mb][i4][1]};
-        *reinterpret_cast<uint2*>(smem + tcol * kPitch + row0) = two;
+        *reinterpret_cast<uint2*>(smem + tcol * kTile + l1_chunk(tcol, row0 >> 3) * 8 + half * 4) = two;
       }
   }
   __syncthreads();
@@ -530,11 +548,13 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
   for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
     const int u = threadIdx.x + k * kGemmNT;
     const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
-    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
+    u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kTile + l1_chunk(r, sl * 8 + c8) * 8);
+    if (r & 16) val = u32x4_t{val.z, val.w, val.x, val.y};   // halves were exchanged on the way in
     __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dz + (int64_t(m0 / 64 + sl) * T_pad + n0 + r) * 64 + c8 * 8));
   }
   __syncthreads();
   // ---- [vocab][token]: neighbouring lanes swap halves so that each writes one (t, t+1) pair ----
+  auto l2_word = [](int voc, int w) -> int { return w ^ ((((voc & 1) << 1) | ((voc >> 2) & 1)) << 4); };
 #pragma unroll
   for (int nb = 0; nb < kNB; ++nb) {
     const int tcol = acc_col(wn, nb, lane);
@@ -550,7 +570,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
           // even lane: row r at columns (tcol, tcol + 1); odd lane: row r + 1 at columns (tcol - 1, tcol)
           const uint32_t outw = odd ? ((got >> 16) | (own & 0xffff0000u)) : ((own & 0xffffu) | (got << 16));
           const int row = acc_row(wm, mb, i4 * 4 + h * 2, lane) + (odd ? 1 : 0);
-          *reinterpret_cast<uint32_t*>(smem + row * kPitch + (tcol & ~1)) = outw;
+          *reinterpret_cast<uint32_t*>(smem + row * kTile + l2_word(row, tcol >> 1) * 2) = outw;
         }
   }
   __syncthreads();
@@ -561,7 +581,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
   for (int k = 0; k < kTile * (kTile / 8) / kGemmNT; ++k) {
     const int u = threadIdx.x + k * kGemmNT;
     const int sl = u >> 11, r = (u >> 3) & 255, c8 = u & 7;
-    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kPitch + (sl * 8 + c8) * 8);
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * kTile + l2_word(r, sl * 32 + c8 * 4) * 2);
     __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dzT_chunk + (int64_t(n0 / 64 + sl) * VC + m_in_chunk + r) * 64 + c8 * 8));
   }
 }
@@ -692,8 +712,8 @@ __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh
   }
 }
 
-// the dz kernel stages a padded 256 x 264 bf16 tile in LDS after its main loop
-static_assert(size_t(kTile) * (kTile + 8) * 2 <= kWarmSinkOff, "the dz staging tile must end before the warm-up sink");
+// the dz kernel stages a 256 x 256 bf16 tile in LDS after its main loop
+static_assert(size_t(kTile) * kTile * 2 <= kWarmSinkOff, "the dz staging tile must end before the warm-up sink");
 constexpr size_t kDzLdsBytes = kGemmLdsBytes;
 
 static aero_status set_lds(const void* fn, size_t bytes = kGemmLdsBytes) {
@@ -733,7 +753,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     if (s_min + 1 > 64 || rows * (s_min + 1) >= (int64_t(1) << 25)) return AERO_ERR_SHAPE;
   }
   // one workgroup per 256 x 256 tile: the tile count must fit a launch grid
-  if (int64_t(p.tiles_v) * (p.T_pad / kTile) >= (int64_t(1) << 31)) return AERO_ERR_SHAPE;
+  if (int64_t(p.tiles_v) * (p.T_pad / kTile) >= (int64_t(1) << 31) - 64) return AERO_ERR_SHAPE;   // grids are rounded up to 64
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kWsAlign || workspace_bytes < p.total)
     return AERO_ERR_WORKSPACE;
   hipStream_t s = as_stream(stream);
@@ -772,7 +792,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
     {
       const int n = p.tiles_v * tiles_t;
       hipLaunchKernelGGL(k_fused_stats, dim3(unsigned(xcd_grid(n))), dim3(kGemmNT), kGemmLdsBytes, s, Wp, hf,
-                         V, H, p.tiles_v, tiles_t, 0, n, p.T_pad, nf, part_m, part_s, part_sz);
+                         V, H, p.tiles_v, p.T_pad, nf, part_m, part_s, part_sz);
     }
     hipLaunchKernelGGL(k_fused_combine, dim3(unsigned(p.T_pad / kCombineTokens)), dim3(kCombineWaves * kWave), 0, s, Wp, hf, H,
                        p.tiles_v, p.T_pad, fidx, nf, part_m, part_s, part_sz, targets, logprob, ent_arr, lse);
@@ -826,10 +846,10 @@ extern "C" aero_status aero_lmhead_logprob_fused(
       const int n = p.tiles_v * tiles_t;
       if (ent)
         hipLaunchKernelGGL(k_fused_dz<true>, dim3(unsigned(xcd_grid(n))), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V,
-                           H, p.tiles_v, tiles_t, 0, n, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
+                           H, p.tiles_v, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
       else
         hipLaunchKernelGGL(k_fused_dz<false>, dim3(unsigned(xcd_grid(n))), dim3(kGemmNT), kDzLdsBytes, s, Wp, hc, V,
-                           H, p.tiles_v, tiles_t, 0, n, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
+                           H, p.tiles_v, p.T_pad, p.VC, nact, gc, lsec, yc, ac, bc, dz, dzT);
     }
     // dz columns [V, V_ld) are zero and WT is zero past V: the contraction runs over the padded vocabulary
     hipLaunchKernelGGL(k_gemm_dh, dim3(unsigned(grid_dh)), dim3(kGemmNT), kGemmLdsBytes, s, dz, WT, p.H_pad, p.V_ld, H,
