@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 # see profiles/logits_path_cfg2_hbm_traffic.txt).  Not a measurement of this run: a figure from
 # that profile, valid only for the kernel sources it was taken on, so it is reported only while
 # their hash still matches and is null otherwise.
-MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8595e+09, "sources_sha256": "c0ac81581d75430026bec98f21e8babfafb9d5822646f5689dfd4b07e6d03609"}}
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8593e+09, "sources_sha256": "e07e5fc25506b03bec83e65206ba643ec90bdbd32752ae1072f8165611f6749b"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of the same kernel sources "
                 "(profiles/logits_path_cfg2_hbm_traffic.txt), not of this run; null once the sources changed")
