@@ -93,7 +93,8 @@ size_t aero_workspace_bytes(int32_t op, int64_t T, int32_t V, int32_t H, int32_t
  *
  * Inputs   rewards[R] f32 (must be exactly 0 or 1 when reject_enable or posterior_mode is
  *          set), lengths[R] i32 (|o_i|, full valid response length), group_offsets[Q+1] i32
- *          (CSR, ascending, off[0] = 0, off[Q] = R, group q = rollouts [off[q], off[q+1])), keep_priority[R] u32 or
+ *          (CSR, ascending, off[0] = 0, off[Q] = R, group q = rollouts [off[q], off[q+1]); every rollout
+ *          belongs to exactly one group: a rollout outside all groups would be left unwritten), keep_priority[R] u32 or
  *          NULL (down-sampling keeps the smallest (key, index) pairs; NULL = index order).
  * Outputs  adv[R] f32, weight[R] f32 (1/(Q * kept_q * lengths[i]) for kept rollouts, else 0),
  *          keep_mask[R] u8, kept_index[R] i32 (first kept_offsets[Q] entries: kept rollout
