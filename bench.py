@@ -33,7 +33,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 # see profiles/logits_path_cfg2_hbm_traffic.txt).  Not a measurement of this run: a figure from
 # that profile, valid only for the kernel sources it was taken on, so it is reported only while
 # their hash still matches and is null otherwise.
-MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8593e+09, "sources_sha256": "e07e5fc25506b03bec83e65206ba643ec90bdbd32752ae1072f8165611f6749b"}}
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8595e+09, "sources_sha256": "7883671bb45187ad48dcd2cefa76fc96502fef0b4a009b88840944513a02474f"},
+                    "cfg2-untouched": {"bytes": 5.7485e+09, "sources_sha256": "7883671bb45187ad48dcd2cefa76fc96502fef0b4a009b88840944513a02474f"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of the same kernel sources "
                 "(profiles/logits_path_cfg2_hbm_traffic.txt), not of this run; null once the sources changed")
@@ -57,7 +58,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=None,
-                    choices=["cfg1", "cfg2", "cfg2-dense", "cfg3", "cfg4", "cfg5", "step"],
+                    choices=["cfg1", "cfg2", "cfg2-dense", "cfg2-untouched", "cfg3", "cfg4", "cfg5", "step"],
                     help="measure this workload alone (default: cfg2 as the headline plus the extras)")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only")
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
@@ -212,10 +213,12 @@ def cpu_baseline_logits(wl, host_old, budget_s):
 def run_logits(args, name, mods, headline):
     torch, ai, aero, binding = mods
     dev = "cuda:0"
-    wl = ai.make_config("cfg2" if name == "cfg2-dense" else name)
+    wl = ai.make_config("cfg2" if name in ("cfg2-dense", "cfg2-untouched") else name)
     if name == "cfg2-dense":   # same tensor shape, every slot a valid token
         wl.lengths[:] = wl.T // wl.R
         wl.token_rollout = np.repeat(np.arange(wl.R, dtype=np.int32), wl.T // wl.R)
+    if name == "cfg2-untouched":   # padding rows marked "leave the gradient row alone" (a consumer that skips them)
+        wl.token_rollout = np.where(wl.token_rollout < 0, binding.AERO_ROW_UNTOUCHED, wl.token_rollout).astype(np.int32)
     T, V, ld, R, Q = wl.T, wl.V, wl.ld, wl.R, wl.Q
     elt = 2 if wl.dtype == "bf16" else 4
 
@@ -324,11 +327,12 @@ def run_logits(args, name, mods, headline):
     trh = wl.token_rollout
     g_rows = int(((trh >= 0) & (adv_h[np.maximum(trh, 0)] != 0)).sum())   # rows that carry signal
     n_grad = int(round(g_rows * (1.0 - clip_frac.item())))   # unclipped rows: read + write
-    n_zero = T - n_grad                                  # write only
+    n_written = T - int((trh == binding.AERO_ROW_UNTOUCHED).sum())   # rows whose gradient row is written at all
+    n_zero = n_written - n_grad                          # write only
     row_bytes = V * elt
     fwd_bytes = n_valid * row_bytes
     bwd_bytes = n_grad * 2 * row_bytes + n_zero * row_bytes
-    single_bytes = n_valid * row_bytes + T * row_bytes   # every valid row read once, every row written once
+    single_bytes = n_valid * row_bytes + n_written * row_bytes   # every valid row read once, every row written once
     valid_only_bytes = 2 * n_valid * row_bytes           # padding rows' zero fill not credited
     fwd_gbs = fwd_bytes / (ms_fwd * 1e-3) / 1e9
     bwd_gbs = bwd_bytes / (ms_bwd * 1e-3) / 1e9
@@ -358,7 +362,8 @@ def run_logits(args, name, mods, headline):
                      "bound": "hbm", "achieved": single_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": single_gbs / HBM_PEAK_GBS, "algorithmic_bytes": single_bytes,
                      "accounting": "every valid row read once (2V bytes) + every row of the tensor written once "
-                                   "(2V bytes; rows without gradient are zero-filled)",
+                                   "(2V bytes; rows without gradient are zero-filled; rows marked untouched, which "
+                                   "only cfg2-untouched has, are not written)",
                      "valid_rows_only": {"algorithmic_bytes": valid_only_bytes, "achieved": valid_only_gbs,
                                          "frac": valid_only_gbs / HBM_PEAK_GBS,
                                          "accounting": "4V bytes per valid row; the zero fill of padding rows is "
@@ -669,7 +674,7 @@ def main():
     out = run_workload(args, "cfg2", mods, headline=True)
     if not args.no_extras:
         out["extra"] = {}
-        for name in ("cfg2-dense", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg2-dense", "cfg2-untouched", "cfg3", "cfg4", "cfg5"):
             torch.cuda.empty_cache()
             t0 = time.time()
             res = run_workload(args, name, mods, headline=False)

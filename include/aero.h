@@ -52,6 +52,12 @@ enum {
  * zero below 3e-8): pass a grad_scale that lifts them, as with any fp16 gradient. */
 enum { AERO_F32 = 0, AERO_BF16 = 1, AERO_F16 = 2 };
 
+/* token_rollout[t] of a token row that belongs to no rollout.  Both are ignored rows; AERO_ROW_UNTOUCHED
+ * additionally tells aero_grpo_loss_bwd (and its _noalloc form) not to write the row's dlogits at all, for
+ * callers whose consumer of the gradient skips padding rows or who keep those rows zero themselves.  Any other
+ * negative value means AERO_ROW_PADDING. */
+enum { AERO_ROW_PADDING = -1, AERO_ROW_UNTOUCHED = -2 };
+
 /* bits of the device error word */
 enum { AERO_DERR_NONBINARY_REWARD = 1, AERO_DERR_BAD_TARGET = 2, AERO_DERR_BAD_ROLLOUT = 4 };
 
@@ -140,7 +146,9 @@ aero_status aero_logprob_fwd(
  *     g_t  = -grad_scale * w * A * rho   if the unclipped branch is active
  *            (A > 0: rho <= 1 + eps_hi;  A < 0: rho >= 1 - eps_lo), else 0
  *     dlogits[t, j] = g_t * (1[j == targets[t]] - exp(z[t,j] - lse[t]))
- *   every other row (padding, ignored, A == 0, w == 0, clipped): dlogits row = +0.
+ *   every other row (padding, ignored, A == 0, w == 0, clipped): dlogits row = +0, except rows with
+ *   token_rollout[t] == AERO_ROW_UNTOUCHED, whose dlogits row is neither read nor written (their
+ *   scalar outputs are 0 like those of any ignored row).
  * Entropy bonus (Table 8 lists a coefficient; it is aggregated with Eq. 2's weights): with
  * entropy_coef = c != 0 every token of a rollout with w != 0, whatever A or the clip decision,
  *     loss -= c * w * H_t,   dlogits[t, j] += grad_scale * c * w * p_j * (ln p_j + H_t),
@@ -158,7 +166,7 @@ aero_status aero_logprob_fwd(
  *          otherwise a forward pass into the workspace precedes the gradient pass.
  * entropy  f32[T] from aero_logprob_fwd; read only when lse != NULL and entropy_coef != 0
  *          (AERO_ERR_NULL if missing then), may be NULL otherwise.
- * old_logprob f32[T]; token_rollout i32[T] (-1 = padding); adv, weight f32[R].
+ * old_logprob f32[T]; token_rollout i32[T] (AERO_ROW_PADDING / AERO_ROW_UNTOUCHED = no rollout); adv, weight f32[R].
  * entropy_coef  c above; 0 switches the term off (NaN: AERO_ERR_SHAPE).
  * kl_coef, ref_logprob  beta above and f32[T] log pi_ref of the sampled tokens; ref_logprob is read
  *          only when kl_coef != 0 (AERO_ERR_NULL if missing then).
@@ -227,7 +235,8 @@ aero_status aero_grpo_loss_bwd_noalloc(
  *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd
  *   (entropy_coef and kl_coef / ref_logprob included: the entropy of the forward part is used,
  *   also when the `entropy` output is NULL).
- * Rows whose target is negative take no part in the contraction (their outputs are 0); a
+ * Rows whose target or rollout index is negative take no part in the contraction (their outputs, the
+ * dhidden row included, are 0; AERO_ROW_UNTOUCHED means the same as AERO_ROW_PADDING here); a
  * target >= V is treated the same way and raises AERO_DERR_BAD_TARGET in err_flag.
  * workspace: aero_workspace_bytes(AERO_OP_LMHEAD_FUSED, T, V, H, R, 0) bytes of device memory,
  * 256-byte aligned, owned by the caller, contents undefined before and after the call.

@@ -18,4 +18,6 @@ from .binding import (  # noqa: F401
     AERO_F32,
     AERO_BF16,
     AERO_F16,
+    AERO_ROW_PADDING,
+    AERO_ROW_UNTOUCHED,
 )

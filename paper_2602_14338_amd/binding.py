@@ -13,6 +13,7 @@ from typing import Optional
 import torch
 
 AERO_F32, AERO_BF16, AERO_F16 = 0, 1, 2
+AERO_ROW_PADDING, AERO_ROW_UNTOUCHED = -1, -2
 OP_GROUP_ADVANTAGE, OP_LOGPROB_FWD, OP_GRPO_LOSS_BWD, OP_LMHEAD_FUSED = 0, 1, 2, 3
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaero_hip.so")

@@ -5,7 +5,7 @@
 //   token terms  one thread per token: ratio, clip decision, loss term, g_t = dloss/dlogprob
 //   loss reduce  one workgroup, fixed summation order (bitwise reproducible), fp64 accumulator
 //   dlogits      one workgroup per row: dz = g_t (onehot - exp(z - lse)); rows with g_t == 0
-//                are not read, they are only filled with +0
+//                are not read, they are only filled with +0 (rows marked AERO_ROW_UNTOUCHED: not even that)
 // Entropy bonus (Table 8 lists a coefficient; aggregated here with Eq. 2's weights): with a
 // coefficient c != 0 every token of a rollout with w != 0 also contributes -c w H_t to the loss
 // and e_t pi_j (ln pi_j + H_t), e_t = grad_scale c w, to its gradient row.  A row is then
@@ -33,7 +33,7 @@ aero_status single_pass_launch(const void* logits, int64_t T, int V, int64_t ld,
 
 // ---------------------------------------------------------------- workspace layout
 struct LossWorkspace {
-  float* g;          // [T] dloss / dlogprob
+  float* g;          // [T] dloss / dlogprob; -0.0 marks a row whose gradient row is not to be written at all
   float* loss_term;  // [T]
   int32_t* flag;     // [T] 0 = no signal, 1 = unclipped, 2 = clipped
   float* lse;        // [T] used when the caller gives none
@@ -43,7 +43,7 @@ struct LossWorkspace {
   float* ea;         // [T] entropy bonus: a_t = grad_scale c w
   float* eb;         // [T] entropy bonus: b_t = a_t (H_t - lse_t) - g_t
   float* ent;        // [T] entropy of the rows when the caller passes no array for it
-  int32_t* counter;  // [3] counters of the streaming single-pass kernel
+  int32_t* counter;  // [4] counters of the streaming single-pass kernel
 };
 constexpr size_t kAlign = 256;
 constexpr size_t seg(int64_t T) { return (size_t(T) * 4 + kAlign - 1) / kAlign * kAlign; }
@@ -129,6 +129,9 @@ __global__ __launch_bounds__(256) void k_token_terms(
       }
     }
   }
+  // the sign of a zero carries "leave the gradient row alone" to the gradient kernels, which have g_t in hand
+  // before anything else: +0 = fill the row with zeros, -0 = do not write it
+  if (g == 0.f) g = (i == AERO_ROW_UNTOUCHED) ? -0.f : 0.f;
   g_out[t] = g;
   term_out[t] = term;
   flag_out[t] = flag;
@@ -212,6 +215,7 @@ __global__ __launch_bounds__(NT) void k_dlogits(
   const int tid = threadIdx.x;
 
   if (g == 0.f && a == 0.f) {   // uniform over the workgroup: nothing to read
+    if (__float_as_uint(g) >> 31) return;   // -0: the row is not to be written
     if constexpr (VEC) {
       u32x4_t* dv = reinterpret_cast<u32x4_t*>(drow);
       const int nvec = V / E;
@@ -288,6 +292,7 @@ __global__ __launch_bounds__(kSegNT) void k_dlogits_seg(
   const int j = nvec * E + threadIdx.x;          // ragged tail, done by segment 0
   const bool tail = seg == 0 && j < V;
   if (g == 0.f && a == 0.f) {   // uniform over the workgroup: nothing to read
+    if (__float_as_uint(g) >> 31) return;   // -0: the row is not to be written
 #pragma unroll
     for (int i = 0; i < kSegVPT; ++i)
       if (k0 + i * kSegNT < nvec) reinterpret_cast<u32x4_t*>(drow)[k0 + i * kSegNT] = u32x4_t{0u, 0u, 0u, 0u};

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
       if (entropy_out) entropy_out[t] = 0.f;
       if (lse_out) lse_out[t] = 0.f;
     }
-    zero_fill();
+    if (i != AERO_ROW_UNTOUCHED) zero_fill();
     return;
   }
 
@@ -224,6 +224,8 @@ __global__ __launch_bounds__(kSpNT) void k_row_single_pass(
 // in which the rows that are read come first and the rows that are only zero-filled last
 // (k_row_order): the memory system then sees a read+write phase followed by a write-only
 // phase instead of a mix of the two, which is worth several percent on padded batches.
+// Rows marked AERO_ROW_UNTOUCHED are in neither part: their gradient row is not written, their
+// scalars are zeroed by k_row_order, and this kernel never sees them.
 // ------------------------------------------------------------------------------------------
 struct RowInfo {
   int y;
@@ -250,28 +252,44 @@ __device__ __forceinline__ RowInfo row_info(int64_t t, int64_t T, int V, int R, 
   return r;
 }
 
-// order[0 .. n) = rows with need, order[n .. T) = the others, each part in no particular order
-// (wave-sized runs are placed by two atomic counters: ctr[1] from the front, ctr[2] from the back).
+// order[0 .. n) = rows with need, order[T - m .. T) = the m rows that are only zero-filled, each part in
+// no particular order (wave-sized runs are placed by two atomic counters: ctr[1] from the front, ctr[2]
+// from the back).  The u rows marked AERO_ROW_UNTOUCHED are placed nowhere (n + m + u = T, the gap in the
+// middle has u entries; ctr[3] counts them) and get their per-row scalars, all zero, here.
 __global__ __launch_bounds__(256) void k_row_order(int64_t T, int V, int R, const int32_t* __restrict__ targets,
                                                    const int32_t* __restrict__ token_rollout,
                                                    const float* __restrict__ adv, const float* __restrict__ weight,
                                                    int stats_all, int every_weighted, int32_t* __restrict__ ctr,
-                                                   int32_t* __restrict__ order) {
+                                                   int32_t* __restrict__ order, float* __restrict__ g_out,
+                                                   float* __restrict__ term_out, int32_t* __restrict__ flag_out,
+                                                   float* __restrict__ logprob_out, float* __restrict__ entropy_out,
+                                                   float* __restrict__ lse_out) {
   const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
   const int lane = threadIdx.x & 63;
   const bool in = t < T;
+  const bool untouched = in && token_rollout[t] == AERO_ROW_UNTOUCHED;
   const bool need = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all, every_weighted != 0).need;
-  const uint64_t m_need = __ballot(in && need), m_rest = __ballot(in && !need);
+  const uint64_t m_need = __ballot(in && need), m_rest = __ballot(in && !need && !untouched);
+  const uint64_t m_unt = __ballot(untouched);
   const uint64_t below = (uint64_t(1) << lane) - 1;
   int base_need = 0, base_rest = 0;
   if (lane == 0) {
     if (m_need) base_need = atomicAdd(ctr + 1, __popcll(m_need));
     if (m_rest) base_rest = atomicAdd(ctr + 2, __popcll(m_rest));
+    if (m_unt) atomicAdd(ctr + 3, __popcll(m_unt));
+  }
+  if (untouched) {
+    g_out[t] = 0.f;
+    term_out[t] = 0.f;
+    flag_out[t] = 0;
+    if (logprob_out) logprob_out[t] = 0.f;
+    if (entropy_out) entropy_out[t] = 0.f;
+    if (lse_out) lse_out[t] = 0.f;
   }
   base_need = __shfl(base_need, 0, kWave);
   base_rest = __shfl(base_rest, 0, kWave);
   if (in && need) order[base_need + __popcll(m_need & below)] = int32_t(t);
-  if (in && !need) order[T - 1 - (base_rest + __popcll(m_rest & below))] = int32_t(t);
+  if (in && !need && !untouched) order[T - 1 - (base_rest + __popcll(m_rest & below))] = int32_t(t);
 }
 
 template <int NV, int NL, bool ENT>
@@ -284,6 +302,11 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     int32_t* __restrict__ flag_out, float* __restrict__ logprob_out, float* __restrict__ entropy_out,
     float* __restrict__ lse_out, uint16_t* dlogits, int32_t* __restrict__ err_flag, int32_t* row_counter,
     const int32_t* __restrict__ order) {
+  // positions 0 .. P of the hand-out skip the gap that the untouched rows leave in the row order
+  const int n_front = row_counter[1];
+  const int n_gap = row_counter[3];
+  const int64_t P = T - n_gap;
+  auto row_at = [&](int64_t p) -> int64_t { return p < P ? order[p < n_front ? p : p + n_gap] : T; };
   __shared__ RowStat lds[2][kSpNT / kWave];   // alternating: one barrier per row is enough
   __shared__ int s_next;
   extern __shared__ __align__(16) u32x4_t slots_raw[];   // NL x kSpNT vectors
@@ -307,11 +330,11 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
 
   // the first gridDim.x positions of the row order are assigned by workgroup id; the counter
   // starts at gridDim.x.  pn = position of the next row, tn = that row (T = none left)
-  int64_t t = order[blockIdx.x];
+  int64_t t = row_at(blockIdx.x);
   if (tid == 0) s_next = atomicAdd(row_counter, 1);
   __syncthreads();
   int64_t pn = s_next;
-  int64_t tn = pn < T ? order[pn] : T;
+  int64_t tn = row_at(pn);
   RowInfo cur = row_info(t, T, V, R, targets, token_rollout, adv, weight, stats_all, ENT);
   if (cur.need) {
     const __amdgpu_buffer_rsrc_t src = row_rsrc(logits, t);
@@ -472,21 +495,22 @@ __global__ __launch_bounds__(kSpNT) void k_row_stream(
     }
     // hand-over: the row after the next one is drawn now (all threads have read s_next)
     __syncthreads();
-    if (tid == 0) s_next = pn < T ? atomicAdd(row_counter, 1) : int(T);
+    if (tid == 0) s_next = pn < P ? atomicAdd(row_counter, 1) : int(T);
     __syncthreads();
     cur = nxt;
     t = tn;
     pn = s_next;
-    tn = pn < T ? order[pn] : T;
+    tn = row_at(pn);
   }
 }
 
 // ctr[0]: row counter of k_row_stream (starts past the rows assigned by workgroup id),
-// ctr[1], ctr[2]: fill counters of k_row_order
+// ctr[1], ctr[2]: fill counters of k_row_order, ctr[3]: its count of untouched rows
 __global__ void k_set_counter(int32_t* ctr, int32_t v) {
   ctr[0] = v;
   ctr[1] = 0;
   ctr[2] = 0;
+  ctr[3] = 0;
 }
 
 // True when the single-pass kernel applies: bf16, 16-byte aligned rows, and a row that fits
@@ -529,7 +553,8 @@ static aero_status single_pass_launch_t(const uint16_t* z, int64_t T, int V, int
   const unsigned grid = unsigned(T < cus ? T : cus);   // one persistent workgroup per CU
   hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(1), 0, s, row_counter, int32_t(grid));
   hipLaunchKernelGGL(k_row_order, dim3(unsigned((T + 255) / 256)), dim3(256), 0, s, T, V, R, targets, token_rollout,
-                     adv, weight, stats_all, ENT ? 1 : 0, row_counter, row_order);
+                     adv, weight, stats_all, ENT ? 1 : 0, row_counter, row_order, g, term, flag, logprob_out,
+                     entropy_out, lse_out);
   hipLaunchKernelGGL((k_row_stream<20, NL, ENT>), dim3(grid), dim3(kSpNT), kLdsBytes, s, z, T, V, ld, targets,
                      old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi, grad_scale, ent_coef, kl_coef, ref_logprob,
                      stats_all, g, term, flag, logprob_out, entropy_out, lse_out, dz, err_flag, row_counter, row_order);

@@ -211,11 +211,22 @@ def elt_rounding(dtype, ref_abs):
 
 
 def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=False, grad_scale=1.0,
-                   expect_clip=False, stats=False, entropy_coef=0.0, kl_coef=0.0, adv_map=None, strict_loss=False):
+                   expect_clip=False, stats=False, entropy_coef=0.0, kl_coef=0.0, adv_map=None, strict_loss=False,
+                   untouched=None):
     """adv_map: replaces the group-relative advantages by adv_map(adv) before both sides see them
     (supplied advantages; e.g. abs makes every term of the loss carry one sign).
-    strict_loss: the loss must meet the pure 1e-4 relative bound (well-conditioned case)."""
+    strict_loss: the loss must meet the pure 1e-4 relative bound (well-conditioned case).
+    untouched: "half" or "all" - that share of the padding rows is handed to the library as
+    AERO_ROW_UNTOUCHED; their gradient rows must keep what the buffer held before the call, everything
+    else must come out as for plain padding (the checker sees plain padding)."""
     host = wl.logits_rows(0, wl.T)
+    tr_gpu = wl.token_rollout.copy()
+    chosen = np.zeros(0, dtype=np.int64)
+    if untouched is not None:
+        pads = np.flatnonzero(wl.token_rollout < 0)
+        chosen = pads if untouched == "all" else pads[::2]
+        assert chosen.size > 0
+        tr_gpu[chosen] = gh.binding.AERO_ROW_UNTOUCHED
     ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams(**params))
     if adv_map is not None:
         ga["adv"] = adv_map(ga["adv"].astype(np.float32)).astype(np.float64)
@@ -231,7 +242,8 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
                             kl_coef=kl_coef, ref_logprob=ref_lp)
     d = gh.logits_to_dev(host, wl.dtype)
     lse_d = gh.dev(lse_ref.astype(np.float32)) if use_oracle_lse else None
-    out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, wl.token_rollout,
+    before = d[torch.from_numpy(chosen).to(gh.DEV)].clone() if (inplace and chosen.size) else None
+    out = gh.run_loss_bwd(d, wl.T, wl.V, wl.ld, wl.targets, lse_d, old, tr_gpu,
                           ga["adv"], ga["weight"], eps=float(eps), grad_scale=grad_scale, inplace=inplace, stats=stats,
                           entropy_coef=entropy_coef,
                           entropy=ent_ref if (use_oracle_lse and entropy_coef != 0.0) else None,
@@ -252,6 +264,14 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
         assert np.abs(lp - ref["logprob"]).max() <= LP_TOL
     dz = gh.to_np64(out["dlogits"])[:, :wl.V]
     want = ref["dlogits"]
+    if chosen.size:   # not written at all: the rows hold what the buffer held before the call
+        rows = out["dlogits"][torch.from_numpy(chosen).to(gh.DEV)]
+        if inplace:
+            as_bits = torch.int32 if wl.dtype == "f32" else torch.int16
+            assert torch.equal(rows.view(as_bits), before.view(as_bits))
+        else:
+            assert (rows.float() == 7.0).all()
+        dz[chosen] = 0.0
     assert np.isfinite(dz).all()
     assert np.abs(dz - want).max() <= DZ_ATOL * max(1.0, grad_scale)    # stated for the unscaled gradient
     # scale of a row: |g_t| for the surrogate, |e_t| (|p ln p| + p H_t) <= |e_t| (1 + H_t) for the entropy term
@@ -259,6 +279,7 @@ def check_loss_bwd(gh, wl, params, sigma_old=0.05, use_oracle_lse=True, inplace=
     bound = 1e-2 * scale[:, None] + elt_rounding(wl.dtype, np.abs(want))
     assert (np.abs(dz - want) <= bound).all()
     dead = (ref["g"] == 0) & (ref["e"] == 0)
+    dead[chosen] = False
     raw = out["dlogits"][:, :wl.V]
     bits = raw.view(torch.int16) if wl.dtype in ("bf16", "f16") else raw.view(torch.int32)
     assert not bits[torch.from_numpy(dead).to(gh.DEV)].any()       # exactly +0, sign bit included
@@ -388,6 +409,26 @@ def test_streaming_kernel_optional_terms_several_rows_per_workgroup(gh):
     assert (ref["e"] == 0).any() and (ref["e"] != 0).any()      # dropped rollouts: rows with neither term
     check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, inplace=True)      # plain variant, in place
     check_loss_bwd(gh, wl(), dict(reject_enable=1), use_oracle_lse=False, inplace=True, stats=True)
+
+
+# 151936 with 384 rows: the streaming kernel with several rows per workgroup; 32768: one workgroup per row;
+# 4999 / 1000: the forward + gradient route (row kernels); with the checker's lse: the gradient kernels alone
+# (151936: one vector per thread in segments).
+@pytest.mark.parametrize("V,ld,slots,dtype", [(151936, 151936, 24, "bf16"), (32768, 32768, 10, "bf16"),
+                                              (4999, 4999, 10, "bf16"), (1000, 1008, 10, "f32"),
+                                              (151936, 151936, 6, "f16")])
+def test_untouched_padding_rows(gh, V, ld, slots, dtype):
+    """Padding rows marked AERO_ROW_UNTOUCHED: no gradient row is written for them (the buffer keeps its
+    contents), their scalar outputs are 0, and every other row - plain padding included - is as before."""
+    def wl():
+        return ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots - 1, dtype=dtype)
+    gs = 4096.0 if dtype == "f16" else 1.0
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, untouched="half", grad_scale=gs)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, untouched="all", stats=True, grad_scale=gs)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=True, untouched="half", grad_scale=gs)
+    check_loss_bwd(gh, wl(), dict(), sigma_old=0.3, use_oracle_lse=False, untouched="half", inplace=True, grad_scale=gs)
+    check_loss_bwd(gh, wl(), dict(reject_enable=1, posterior_mode=1), sigma_old=0.3, use_oracle_lse=False,
+                   untouched="all", entropy_coef=1e-3, kl_coef=0.04, grad_scale=gs)
 
 
 # Well-conditioned losses: every term carries one sign, so nothing cancels and the stated
