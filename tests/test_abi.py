@@ -52,3 +52,30 @@ def test_status_strings_and_workspace_sizes_on_host():
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2602_14338_amd", "binding.py")).read()
     assert "oracle" not in src and "numpy" not in src
+
+
+def test_header_is_plain_c_and_its_constants_match_the_binding(tmp_path):
+    """include/aero.h compiles as C99 on its own, and every constant the binding re-states has the
+    header's value."""
+    import subprocess
+    from paper_2602_14338_amd import binding
+    names = ["AERO_F32", "AERO_BF16", "AERO_F16", "AERO_ROW_PADDING", "AERO_ROW_UNTOUCHED",
+             "AERO_OP_GROUP_ADVANTAGE", "AERO_OP_LOGPROB_FWD", "AERO_OP_GRPO_LOSS_BWD", "AERO_OP_LMHEAD_FUSED",
+             "AERO_NOALLOC_MAX_T"]
+    src = tmp_path / "consts.c"
+    src.write_text('#include "aero.h"\n#include <stdio.h>\nint main(void) {\n' +
+                   "".join('  printf("%s %%ld\\n", (long)%s);\n' % (n, n) for n in names) +
+                   '  printf("sizeof_params %ld\\n", (long)sizeof(aero_adv_params));\n  return 0;\n}\n')
+    exe = tmp_path / "consts"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    assert int(got["AERO_F32"]) == binding.AERO_F32 and int(got["AERO_BF16"]) == binding.AERO_BF16
+    assert int(got["AERO_F16"]) == binding.AERO_F16
+    assert int(got["AERO_ROW_PADDING"]) == binding.AERO_ROW_PADDING == -1
+    assert int(got["AERO_ROW_UNTOUCHED"]) == binding.AERO_ROW_UNTOUCHED == -2
+    assert [int(got[n]) for n in names[5:9]] == [binding.OP_GROUP_ADVANTAGE, binding.OP_LOGPROB_FWD,
+                                                 binding.OP_GRPO_LOSS_BWD, binding.OP_LMHEAD_FUSED]
+    assert int(got["sizeof_params"]) == ctypes.sizeof(binding._AdvParamsC)
+    assert int(got["AERO_NOALLOC_MAX_T"]) == 65536
