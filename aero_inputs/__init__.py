@@ -13,7 +13,7 @@ tokens with padding removed, bf16 activations, clip range 0.2).  Every draw come
 from ``numpy.random.default_rng`` keyed by ``(seed, stream, block)`` so that any
 block of rows can be regenerated on its own and in parallel.
 """
-from .bf16 import f32_to_bf16_bits, f32_to_f16_bits
+from .bf16 import f32_to_bf16_bits, f32_to_f16_bits, f32_to_f8e4m3_bits
 from .workloads import (
     ADV_PARAM_DEFAULTS,
     LogitsWorkload,
@@ -36,4 +36,5 @@ __all__ = [
     "normal_rows",
     "f32_to_bf16_bits",
     "f32_to_f16_bits",
+    "f32_to_f8e4m3_bits",
 ]

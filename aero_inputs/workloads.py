@@ -19,7 +19,7 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-from .bf16 import f32_to_bf16_bits, f32_to_f16_bits
+from .bf16 import f32_to_bf16_bits, f32_to_f16_bits, f32_to_f8e4m3_bits
 
 ROWS_PER_BLOCK = 64
 
@@ -43,19 +43,21 @@ def normal_rows(seed: int, stream: int, r0: int, r1: int, ncols: int, sigma: flo
                 threads: int = 1) -> np.ndarray:
     """Rows ``[r0, r1)`` of an i.i.d. N(0, sigma^2) matrix with ``ncols`` columns.
 
-    ``dtype`` is ``"f32"`` (float32 values), ``"bf16"`` or ``"f16"`` (uint16 bit patterns, RNE).
+    ``dtype`` is ``"f32"`` (float32 values), ``"bf16"`` or ``"f16"`` (uint16 bit patterns, RNE) or
+    ``"f8e4m3"`` (uint8 bit patterns, RNE).
     Row ``r`` always comes from block ``r // ROWS_PER_BLOCK`` of the keyed stream, so
     the result does not depend on how the rows are requested.  With ``ld > ncols``
     the trailing columns hold +inf: they are not part of the matrix and a reader that
     touches them is wrong.
     """
     ld = ncols if ld is None else int(ld)
-    np_dt = np.float32 if dtype == "f32" else np.uint16
+    np_dt = np.float32 if dtype == "f32" else np.uint8 if dtype == "f8e4m3" else np.uint16
     if out is None:
         out = np.empty((r1 - r0, ld), dtype=np_dt)
     assert out.shape == (r1 - r0, ld) and out.dtype == np_dt
     if ld > ncols:
-        out[:, ncols:] = np.inf if dtype == "f32" else np.uint16(0x7F80 if dtype == "bf16" else 0x7C00)
+        out[:, ncols:] = (np.inf if dtype == "f32" else np.uint8(0x7F) if dtype == "f8e4m3" else     # f8: NaN
+                          np.uint16(0x7F80 if dtype == "bf16" else 0x7C00))
 
     def do_block(b: int) -> None:
         lo, hi = b * ROWS_PER_BLOCK, (b + 1) * ROWS_PER_BLOCK
@@ -64,7 +66,8 @@ def normal_rows(seed: int, stream: int, r0: int, r1: int, ncols: int, sigma: flo
         s0, s1 = max(lo, r0), min(hi, r1)
         part = x[s0 - lo:s1 - lo]
         out[s0 - r0:s1 - r0, :ncols] = (part if dtype == "f32" else
-                                        f32_to_bf16_bits(part) if dtype == "bf16" else f32_to_f16_bits(part))
+                                        f32_to_bf16_bits(part) if dtype == "bf16" else
+                                        f32_to_f8e4m3_bits(part) if dtype == "f8e4m3" else f32_to_f16_bits(part))
 
     blocks = range(r0 // ROWS_PER_BLOCK, (r1 - 1) // ROWS_PER_BLOCK + 1) if r1 > r0 else []
     if threads > 1:
@@ -113,7 +116,7 @@ class _Groups:
 class LogitsWorkload(_Groups):
     name: str = ""
     seed: int = 0
-    dtype: str = "bf16"            # "bf16" | "f16" | "f32"
+    dtype: str = "bf16"            # "bf16" | "f16" | "f8e4m3" | "f32"
     T: int = 0
     V: int = 0
     ld: int = 0

@@ -55,8 +55,33 @@ class AdvParams:
     beta0: float = 1.0
 
 
+def _f8e4m3_values() -> np.ndarray:
+    """The 256 values of the 8-bit float with 4 exponent bits (bias 7) and 3 mantissa bits, in the
+    variant without infinities: sign.1111.111 is NaN, every other pattern is finite (largest 448 =
+    1.75 * 2^8), exponent field 0 holds zero and the subnormals m * 2^-9."""
+    t = np.empty(256, dtype=np.float64)
+    for b in range(256):
+        e, m = (b >> 3) & 0xF, b & 0x7
+        if e == 0xF and m == 0x7:
+            v = np.nan
+        elif e == 0:
+            v = m * 2.0 ** -9
+        else:
+            v = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        t[b] = -v if b & 0x80 else v
+    return t
+
+
+_F8E4M3 = _f8e4m3_values()
+
+
 def widen(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Stored values -> float64, exactly.  dtype: "bf16" or "f16" (uint16 bits), "f32", "f64"."""
+    """Stored values -> float64, exactly.  dtype: "bf16" or "f16" (uint16 bits), "f8e4m3" (uint8 bits),
+    "f32", "f64"."""
+    if dtype == "f8e4m3":
+        x = np.ascontiguousarray(x)
+        assert x.dtype == np.uint8
+        return _F8E4M3[x]
     if dtype == "bf16":
         x = np.ascontiguousarray(x)
         assert x.dtype == np.uint16

@@ -71,6 +71,31 @@ def test_f16_roundtrip_matches_torch():
         [1.0, -2.0, 2.0 ** -24, 65504.0]
 
 
+def test_f8e4m3_roundtrip_matches_torch():
+    """8-bit float storage (4 exponent, 3 mantissa bits, no infinities): the checker's widening of all
+    256 patterns and the generator's rounding against torch's conversions, bit for bit; the values
+    the format is defined by (largest 448, smallest subnormal 2^-9, one NaN per sign); ties go to the
+    even mantissa, also across a power of two and into the subnormals."""
+    every = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(every).view(torch.float8_e4m3fn).float().double().numpy()
+    got = orc.widen(every, "f8e4m3")
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.isnan(got).sum() == 2
+    assert np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+    assert orc.widen(np.array([0x7E, 0x01, 0x38, 0xC0, 0x08, 0x00, 0x80], np.uint8), "f8e4m3").tolist() == \
+        [448.0, 2.0 ** -9, 1.0, -2.0, 2.0 ** -6, 0.0, -0.0]
+    assert np.all(np.diff(got[:127]) > 0)                     # codes 0..126 ascend in value
+    rng = np.random.default_rng(3)
+    x = np.concatenate([(rng.standard_normal(200000) * 3).astype(np.float32),
+                        (rng.standard_normal(20000) * 0.01).astype(np.float32)])
+    mid = ((got[:126] + got[1:127]) / 2).astype(np.float32)   # every midpoint of two neighbours is a float32
+    x = np.concatenate([x, mid, -mid, got[:127].astype(np.float32), np.float32([440.0, 447.9, 448.0, -448.0])])
+    bits = ai.f32_to_f8e4m3_bits(x)
+    tb = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(bits, tb)
+    assert ai.f32_to_f8e4m3_bits(np.float32([1.0625, 1.1875, 0.0009765625, 1000.0, -1000.0])).tolist() == \
+        [0x38, 0x3A, 0x00, 0x7E, 0xFE]                        # ties to even; 2^-10 -> 0; beyond the range -> 448
+
+
 # ------------------------------------------------------------------ group statistics
 
 @pytest.mark.parametrize("n", range(2, 17))
