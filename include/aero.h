@@ -47,10 +47,14 @@ enum {
   AERO_ERR_LIMIT = 7       /* size beyond the fixed capacity of an entry point that owns its scratch */
 };
 
-/* Storage types of logits / dlogits.  AERO_F16 (IEEE binary16) is accepted by aero_logprob_fwd and
- * aero_grpo_loss_bwd only; its gradient entries round to the fp16 grid (subnormals below 6.1e-5,
- * zero below 3e-8): pass a grad_scale that lifts them, as with any fp16 gradient. */
-enum { AERO_F32 = 0, AERO_BF16 = 1, AERO_F16 = 2 };
+/* Storage types of logits / dlogits.  AERO_F16 (IEEE binary16) and AERO_F8E4M3 are accepted by
+ * aero_logprob_fwd and aero_grpo_loss_bwd only.  fp16 gradient entries round to the fp16 grid (subnormals
+ * below 6.1e-5, zero below 3e-8): pass a grad_scale that lifts them, as with any fp16 gradient.
+ * AERO_F8E4M3 is the 8-bit float with 4 exponent bits (bias 7) and 3 mantissa bits in the variant without
+ * infinities (sign.1111.111 is NaN, largest finite value 448, subnormals are multiples of 2^-9); gradient
+ * entries are rounded to nearest even on that grid and saturate at +-448, so a grad_scale is needed all the
+ * more.  All arithmetic is fp32 whatever the storage type. */
+enum { AERO_F32 = 0, AERO_BF16 = 1, AERO_F16 = 2, AERO_F8E4M3 = 3 };
 
 /* token_rollout[t] of a token row that belongs to no rollout.  Both are ignored rows; AERO_ROW_UNTOUCHED
  * additionally tells aero_grpo_loss_bwd (and its _noalloc form) not to write the row's dlogits at all, for
@@ -124,7 +128,7 @@ aero_status aero_group_advantage(
  *   lse[t] = log sum_j exp z[t,j],  logprob[t] = z[t, targets[t]] - lse[t],
  *   entropy[t] = lse[t] - sum_j softmax(z[t])_j z[t,j]          (natural log, temperature 1)
  *
- * logits   [T, ld] row-major, dtype AERO_BF16, AERO_F16 or AERO_F32, ld >= V; columns >= V are never
+ * logits   [T, ld] row-major, dtype AERO_BF16, AERO_F16, AERO_F8E4M3 or AERO_F32, ld >= V; columns >= V are never
  *          read.  Any alignment works; rows whose base and ld*sizeof(elt) are multiples of
  *          16 bytes take the 128-bit load path.
  * targets  i32[T] sampled-token ids; row_active u8[T] or NULL.

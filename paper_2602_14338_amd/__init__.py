@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     AERO_F32,
     AERO_BF16,
     AERO_F16,
+    AERO_F8E4M3,
     AERO_ROW_PADDING,
     AERO_ROW_UNTOUCHED,
 )

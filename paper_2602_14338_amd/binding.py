@@ -12,7 +12,7 @@ from typing import Optional
 
 import torch
 
-AERO_F32, AERO_BF16, AERO_F16 = 0, 1, 2
+AERO_F32, AERO_BF16, AERO_F16, AERO_F8E4M3 = 0, 1, 2, 3
 AERO_ROW_PADDING, AERO_ROW_UNTOUCHED = -1, -2
 OP_GROUP_ADVANTAGE, OP_LOGPROB_FWD, OP_GRPO_LOSS_BWD, OP_LMHEAD_FUSED = 0, 1, 2, 3
 
@@ -116,6 +116,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return AERO_F32
     if t.dtype == torch.float16:
         return AERO_F16
+    if t.dtype == torch.float8_e4m3fn:
+        return AERO_F8E4M3
     raise AeroError(f"unsupported dtype {t.dtype}")
 
 

@@ -45,20 +45,42 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
 }
 __device__ __forceinline__ uint16_t f32_to_f16(float x) { return uint16_t(pack_f16x2(x, 0.f) & 0xffffu); }
 
+// 8-bit float storage, 4 exponent and 3 mantissa bits, no infinities (largest finite value 448): widening is
+// exact; narrowing rounds to nearest even, keeps subnormals (multiples of 2^-9) and saturates beyond +-448.
+__device__ __forceinline__ float f8_to_f32(uint8_t b) { return __builtin_amdgcn_cvt_f32_fp8(int(b), 0); }
+__device__ __forceinline__ uint32_t pack_f8x4(float a, float b, float c, float d) {
+  constexpr float kMax = 448.f;
+  a = __builtin_amdgcn_fmed3f(a, -kMax, kMax);
+  b = __builtin_amdgcn_fmed3f(b, -kMax, kMax);
+  c = __builtin_amdgcn_fmed3f(c, -kMax, kMax);
+  d = __builtin_amdgcn_fmed3f(d, -kMax, kMax);
+  int p = 0;
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, p, false);   // low half of the word
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, p, true);    // high half
+  return uint32_t(p);
+}
+__device__ __forceinline__ uint8_t f32_to_f8(float x) { return uint8_t(pack_f8x4(x, 0.f, 0.f, 0.f) & 0xffu); }
+
 // Storage type tags (the values of the public dtype codes) and what depends on them.
-constexpr int kF32 = AERO_F32, kBF16 = AERO_BF16, kF16 = AERO_F16;
+constexpr int kF32 = AERO_F32, kBF16 = AERO_BF16, kF16 = AERO_F16, kF8 = AERO_F8E4M3;
 template <int DT> struct Storage {
-  static constexpr int kBytes = DT == kF32 ? 4 : 2;
+  static constexpr int kBytes = DT == kF32 ? 4 : DT == kF8 ? 1 : 2;
   static constexpr int kPerVec = 16 / kBytes;   // elements per 16-byte vector
 };
+inline bool storage_dtype_ok(int32_t dtype) {
+  return dtype == AERO_BF16 || dtype == AERO_F32 || dtype == AERO_F16 || dtype == AERO_F8E4M3;
+}
+inline size_t storage_bytes(int32_t dtype) { return dtype == AERO_F32 ? 4 : dtype == AERO_F8E4M3 ? 1 : 2; }
 template <int DT> __device__ __forceinline__ float load_elt(const void* row, int64_t j) {
   if constexpr (DT == kBF16) return bf16_to_f32(reinterpret_cast<const uint16_t*>(row)[j]);
   else if constexpr (DT == kF16) return f16_to_f32(reinterpret_cast<const uint16_t*>(row)[j]);
+  else if constexpr (DT == kF8) return f8_to_f32(reinterpret_cast<const uint8_t*>(row)[j]);
   else return reinterpret_cast<const float*>(row)[j];
 }
 template <int DT> __device__ __forceinline__ void store_elt(void* row, int64_t j, float x) {
   if constexpr (DT == kBF16) reinterpret_cast<uint16_t*>(row)[j] = f32_to_bf16(x);
   else if constexpr (DT == kF16) reinterpret_cast<uint16_t*>(row)[j] = f32_to_f16(x);
+  else if constexpr (DT == kF8) reinterpret_cast<uint8_t*>(row)[j] = f32_to_f8(x);
   else reinterpret_cast<float*>(row)[j] = x;
 }
 
@@ -161,10 +183,22 @@ __device__ __forceinline__ void unpack8_f16(const u32x4_t& v, float (&z)[8]) {
   }
 }
 
-// One 16-byte vector of stored logits -> floats (8 for the 2-byte types, 4 for fp32) and back.
+__device__ __forceinline__ void unpack16_f8(const u32x4_t& v, float (&z)[16]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8(int(w[k]), false);
+    const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8(int(w[k]), true);
+    z[4 * k] = lo.x; z[4 * k + 1] = lo.y;
+    z[4 * k + 2] = hi.x; z[4 * k + 3] = hi.y;
+  }
+}
+
+// One 16-byte vector of stored logits -> floats (16 for the 8-bit type, 8 for the 2-byte types, 4 for fp32) and back.
 template <int DT> __device__ __forceinline__ void unpack_vec(const u32x4_t& v, float (&z)[Storage<DT>::kPerVec]) {
   if constexpr (DT == kBF16) unpack8(v, z);
   else if constexpr (DT == kF16) unpack8_f16(v, z);
+  else if constexpr (DT == kF8) unpack16_f8(v, z);
   else {
     z[0] = __uint_as_float(v.x); z[1] = __uint_as_float(v.y);
     z[2] = __uint_as_float(v.z); z[3] = __uint_as_float(v.w);
@@ -178,6 +212,9 @@ template <int DT> __device__ __forceinline__ u32x4_t pack_vec(const float (&d)[S
   } else if constexpr (DT == kF16) {
     o.x = pack_f16x2(d[0], d[1]); o.y = pack_f16x2(d[2], d[3]);
     o.z = pack_f16x2(d[4], d[5]); o.w = pack_f16x2(d[6], d[7]);
+  } else if constexpr (DT == kF8) {
+    o.x = pack_f8x4(d[0], d[1], d[2], d[3]);     o.y = pack_f8x4(d[4], d[5], d[6], d[7]);
+    o.z = pack_f8x4(d[8], d[9], d[10], d[11]);   o.w = pack_f8x4(d[12], d[13], d[14], d[15]);
   } else {
     o.x = __float_as_uint(d[0]); o.y = __float_as_uint(d[1]);
     o.z = __float_as_uint(d[2]); o.w = __float_as_uint(d[3]);

@@ -354,6 +354,9 @@ static void dispatch_dlogits_dtype(int32_t dtype, bool vec, const void* logits, 
   } else if (dtype == AERO_F16) {
     if (vec) dispatch_dlogits<kF16, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
     else dispatch_dlogits<kF16, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+  } else if (dtype == AERO_F8E4M3) {
+    if (vec) dispatch_dlogits<kF8, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
+    else dispatch_dlogits<kF8, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
   } else {
     if (vec) dispatch_dlogits<kF32, true, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
     else dispatch_dlogits<kF32, false, ENT>(logits, T, V, ld, targets, lse, g, ea, eb, dlogits, s);
@@ -389,7 +392,7 @@ static aero_status loss_bwd_run(
   if (kl_coef != 0.f && T > 0 && !ref_logprob) return AERO_ERR_NULL;
   if (lse && ent && !entropy) return AERO_ERR_NULL;             // H_t must come with the given lse
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || R < 0 || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
-  if (dtype != AERO_BF16 && dtype != AERO_F32 && dtype != AERO_F16) return AERO_ERR_DTYPE;
+  if (!storage_dtype_ok(dtype)) return AERO_ERR_DTYPE;
   if (!loss) return AERO_ERR_NULL;
   hipStream_t s = as_stream(stream);
   if (T > 0 && (!logits || !targets || !old_logprob || !token_rollout || !adv || !weight)) return AERO_ERR_NULL;
@@ -432,14 +435,15 @@ static aero_status loss_bwd_run(
     return AERO_ERR_NULL;   // these outputs exist only when the statistics are computed here
   }
   auto token_terms = dtype == AERO_BF16 ? k_token_terms<kBF16, false>
-                     : dtype == AERO_F16 ? k_token_terms<kF16, false> : k_token_terms<kF32, false>;
+                     : dtype == AERO_F16 ? k_token_terms<kF16, false>
+                     : dtype == AERO_F8E4M3 ? k_token_terms<kF8, false> : k_token_terms<kF32, false>;
   hipLaunchKernelGGL(token_terms, dim3(blocks), dim3(256), 0, s, logits, T, V, ld, targets, lse,
                      static_cast<const float*>(nullptr), old_logprob, token_rollout, adv, weight, R, eps_lo, eps_hi,
                      grad_scale, entropy_coef, entropy, kl_coef, ref_logprob, ws.g, ws.loss_term, ws.flag,
                      ent ? ws.ea : nullptr, ent ? ws.eb : nullptr, lp_dst, err_flag);
   hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(kReduceNT), 0, s, ws.loss_term, ws.flag, T, loss, clip_frac);
   if (dlogits) {
-    const size_t elt = dtype == AERO_F32 ? 4 : 2;
+    const size_t elt = storage_bytes(dtype);
     const bool vec = reinterpret_cast<uintptr_t>(logits) % 16 == 0 && reinterpret_cast<uintptr_t>(dlogits) % 16 == 0 &&
                      (size_t(ld) * elt) % 16 == 0;
     if (ent) dispatch_dlogits_dtype<true>(dtype, vec, logits, T, V, ld, targets, lse, ws.g, ws.ea, ws.eb, dlogits, s);

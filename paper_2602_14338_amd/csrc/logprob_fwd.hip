@@ -109,7 +109,7 @@ aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int
                                const int32_t* targets, const uint8_t* row_active, float* logprob,
                                float* entropy, float* lse, int32_t* err_flag, hipStream_t s) {
   if (T == 0) return AERO_OK;
-  const size_t elt = dtype == AERO_F32 ? 4 : 2;
+  const size_t elt = storage_bytes(dtype);
   const bool vec = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((size_t(ld) * elt) % 16 == 0);
   if (dtype == AERO_BF16) {
     if (vec) dispatch_nt<kBF16, true>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
@@ -117,6 +117,9 @@ aero_status logprob_fwd_launch(const void* logits, int32_t dtype, int64_t T, int
   } else if (dtype == AERO_F16) {
     if (vec) dispatch_nt<kF16, true>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
     else dispatch_nt<kF16, false>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
+  } else if (dtype == AERO_F8E4M3) {
+    if (vec) dispatch_nt<kF8, true>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
+    else dispatch_nt<kF8, false>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
   } else {
     if (vec) dispatch_nt<kF32, true>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
     else dispatch_nt<kF32, false>(logits, T, V, ld, targets, row_active, logprob, entropy, lse, err_flag, s);
@@ -131,7 +134,7 @@ extern "C" aero_status aero_logprob_fwd(const void* logits, int32_t dtype, int64
                                         float* logprob, float* entropy, float* lse,
                                         int32_t* err_flag, void* stream) {
   if (T < 0 || V < 1 || V > (1 << 24) || ld < V || T > 0x7fffffffLL) return AERO_ERR_SHAPE;
-  if (dtype != AERO_BF16 && dtype != AERO_F32 && dtype != AERO_F16) return AERO_ERR_DTYPE;
+  if (!aero::storage_dtype_ok(dtype)) return AERO_ERR_DTYPE;
   if (T == 0) return AERO_OK;
   if (!logits || !targets || !logprob || !lse) return AERO_ERR_NULL;
   return aero::logprob_fwd_launch(logits, dtype, T, V, ld, targets, row_active, logprob, entropy, lse,

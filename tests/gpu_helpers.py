@@ -14,16 +14,46 @@ def dev(x):
 
 
 def logits_to_dev(arr, dtype):
-    """Host logits (float32 values, or bf16 / fp16 bit patterns in uint16) -> device tensor."""
+    """Host logits (float32 values, bf16 / fp16 bit patterns in uint16, 8-bit float patterns in uint8)
+    -> device tensor."""
+    if dtype == "f8e4m3":
+        return torch.from_numpy(arr).to(DEV).view(torch.float8_e4m3fn)
     if dtype in ("bf16", "f16"):
         return torch.from_numpy(arr.view(np.int16)).to(DEV).view(torch.bfloat16 if dtype == "bf16" else torch.float16)
     return torch.from_numpy(arr).to(DEV)
 
 
 def to_np64(t):
+    if t.dtype == torch.float8_e4m3fn:     # widened on the host by the checker's table
+        from oracle import aero_oracle as orc
+        return orc.widen(t.view(torch.uint8).cpu().numpy(), "f8e4m3")
     if t.dtype in (torch.bfloat16, torch.float16):
         return t.float().cpu().numpy().astype(np.float64)
     return t.cpu().numpy().astype(np.float64)
+
+
+SEVEN_F8 = 0x4E    # 7.0 = 1.75 * 2^2 in the 8-bit float format
+
+
+def raw_bits(t):
+    """Integer view of a stored tensor (for indexing and bit comparisons; some 8-bit float kernels
+    of the tensor library may be missing, integer ones are not)."""
+    if t.dtype == torch.float8_e4m3fn:
+        return t.view(torch.uint8)
+    return t.view(torch.int32) if t.dtype == torch.float32 else t.view(torch.int16)
+
+
+def full_like_seven(t):
+    """A buffer of the same shape and type filled with 7.0 (to see what a call leaves unwritten)."""
+    if t.dtype == torch.float8_e4m3fn:
+        return torch.full(t.shape, SEVEN_F8, dtype=torch.uint8, device=t.device).view(torch.float8_e4m3fn)
+    return torch.full_like(t, 7.0)
+
+
+def all_seven(t):
+    if t.dtype == torch.float8_e4m3fn:
+        return bool((t.view(torch.uint8) == SEVEN_F8).all())
+    return bool((t.float() == 7.0).all())
 
 
 def run_group_advantage(wl_or_arrays, params: dict, keys="wl"):
@@ -77,7 +107,7 @@ def run_loss_bwd(logits_d, T, V, ld, targets, lse_d, old_lp, token_rollout, adv,
     elif inplace:
         dl = logits_d
     else:
-        dl = torch.full_like(logits_d, 7.0)
+        dl = full_like_seven(logits_d)
     err = torch.zeros(1, dtype=torch.int32, device=DEV)
     ent_out = torch.full((T,), 7.0, device=DEV) if stats else None
     lse_out = torch.full((T,), 7.0, device=DEV) if stats else None

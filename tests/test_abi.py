@@ -59,7 +59,7 @@ def test_header_is_plain_c_and_its_constants_match_the_binding(tmp_path):
     header's value."""
     import subprocess
     from paper_2602_14338_amd import binding
-    names = ["AERO_F32", "AERO_BF16", "AERO_F16", "AERO_ROW_PADDING", "AERO_ROW_UNTOUCHED",
+    names = ["AERO_F32", "AERO_BF16", "AERO_F16", "AERO_F8E4M3", "AERO_ROW_PADDING", "AERO_ROW_UNTOUCHED",
              "AERO_OP_GROUP_ADVANTAGE", "AERO_OP_LOGPROB_FWD", "AERO_OP_GRPO_LOSS_BWD", "AERO_OP_LMHEAD_FUSED",
              "AERO_NOALLOC_MAX_T"]
     src = tmp_path / "consts.c"
@@ -75,7 +75,8 @@ def test_header_is_plain_c_and_its_constants_match_the_binding(tmp_path):
     assert int(got["AERO_F16"]) == binding.AERO_F16
     assert int(got["AERO_ROW_PADDING"]) == binding.AERO_ROW_PADDING == -1
     assert int(got["AERO_ROW_UNTOUCHED"]) == binding.AERO_ROW_UNTOUCHED == -2
-    assert [int(got[n]) for n in names[5:9]] == [binding.OP_GROUP_ADVANTAGE, binding.OP_LOGPROB_FWD,
+    assert int(got["AERO_F8E4M3"]) == binding.AERO_F8E4M3
+    assert [int(got[n]) for n in names[6:10]] == [binding.OP_GROUP_ADVANTAGE, binding.OP_LOGPROB_FWD,
                                                  binding.OP_GRPO_LOSS_BWD, binding.OP_LMHEAD_FUSED]
     assert int(got["sizeof_params"]) == ctypes.sizeof(binding._AdvParamsC)
     assert int(got["AERO_NOALLOC_MAX_T"]) == 65536
