@@ -10,8 +10,11 @@ Prints ONE JSON line.  Its top level is the headline workload: tokens/s (valid t
 second), the roofline of the dominant kernel measured with events on the launch stream, and the
 float64 CPU checker timed on a bounded sample of the same workload as a baseline.  Under
 "extra" the same process measures, each with its own roofline and CPU baseline: cfg2 with every
-slot valid, the AERO-pruned ragged batch (cfg3) and the two LM-head-fused workloads (cfg4,
-cfg5).  `--workload X` measures X alone.
+slot valid, cfg2 with its padding rows marked "leave the gradient row alone", the AERO-pruned
+ragged batch (cfg3), the two LM-head-fused workloads (cfg4, cfg5), and one whole policy-update
+step of 256 queries under plain grouping and under AERO's allocation + curation ("step": rollouts
+and tokens trained on, time of both, CPU baseline; no roofline of its own, its calls are the cfg2 /
+cfg3 kind).  `--workload X` measures X alone.
 """
 import argparse
 import json
@@ -674,7 +677,7 @@ def main():
     out = run_workload(args, "cfg2", mods, headline=True)
     if not args.no_extras:
         out["extra"] = {}
-        for name in ("cfg2-dense", "cfg2-untouched", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg2-dense", "cfg2-untouched", "cfg3", "cfg4", "cfg5", "step"):
             torch.cuda.empty_cache()
             t0 = time.time()
             res = run_workload(args, name, mods, headline=False)
