@@ -132,6 +132,30 @@ def logits_full_size(gh, name, params):
     assert (np.abs(dz1 - want) <= 1e-2 * np.abs(sub["g"])[:, None] + np.abs(want) * 2.0 ** -8 + 1e-30).all()
     nz_rows = (one["dlogits"].view(torch.int16) != 0).any(dim=1).cpu().numpy()
     assert not nz_rows[~signal].any() and nz_rows[g_ref != 0].all()
+
+    # padding rows marked "leave the gradient row alone": those rows keep the buffer's contents, every other
+    # row, the loss and the statistics come out bit for bit as with plain padding (both routes)
+    pads = np.nonzero(tr < 0)[0]
+    if pads.size:
+        tr_u = np.where(tr < 0, gh.binding.AERO_ROW_UNTOUCHED, tr).astype(np.int32)
+        pads_d, rest_d = torch.from_numpy(pads).to(gh.DEV), torch.from_numpy(np.nonzero(tr >= 0)[0]).to(gh.DEV)
+        for lse_arg in (None, lse):
+            u = gh.run_loss_bwd(logits, T, V, ld, wl.targets, lse_arg, old, tr_u, ga["adv"], ga["weight"],
+                                eps=float(eps), stats=lse_arg is None)
+            assert u["err"] == 0
+            if lse_arg is None:
+                assert u["loss"].item() == one["loss"].item()
+            else:       # the forward call's lse differs from the single-pass one by fp32 rounding
+                gh.assert_loss(u["loss"].item(), loss_ref, terms)
+            assert gh.all_seven(u["dlogits"][pads_d])
+            assert torch.equal(u["dlogits"][rest_d].view(torch.int16), one["dlogits"][rest_d].view(torch.int16)) \
+                if lse_arg is None else \
+                bool(((u["dlogits"][rest_d].float() - one["dlogits"][rest_d].float()).abs()
+                      <= 2.0 ** -7 * one["dlogits"][rest_d].float().abs() + 1e-12).all())
+            if lse_arg is None:
+                for key in ("logprob", "entropy", "lse"):
+                    assert torch.equal(u[key], one[key]), key
+            del u
     del one
     torch.cuda.empty_cache()
 
