@@ -11,7 +11,8 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and the call returns without synchronising.  Calls that share a workspace must be
  *     ordered on one stream.
- *   - Outputs are fully overwritten.  Nullable arguments are marked.
+ *   - Outputs are fully overwritten (one exception, on request: dlogits rows of token rows marked
+ *     AERO_ROW_UNTOUCHED).  Nullable arguments are marked.
  *   - Shape errors that can be seen from host scalars return a status code and enqueue
  *     nothing.  Errors that depend on device data never fault; a bit is OR-ed into the
  *     optional device word `err_flag`, which the caller zeroes:
@@ -19,8 +20,9 @@
  *       a reward other than 0 or 1 where binary ones are required: the group is still
  *       processed, with every reward other than exactly 1 counted as incorrect.
  *   - "Ignored row": a token row with a negative sampled-token id, a negative rollout
- *     index, or row_active == 0.  It is not read, its outputs are 0 (gradient rows +0), and
- *     nothing about it is flagged, whatever its other fields hold.
+ *     index, or row_active == 0.  It is not read, its outputs are 0 (gradient rows +0, or left as
+ *     they are when the rollout index is AERO_ROW_UNTOUCHED), and nothing about it is flagged,
+ *     whatever its other fields hold.
  *   - Logits (and hidden states / weights) must be finite.  An infinite or NaN logit gives NaN
  *     statistics for its row (the entropy term contains 0 * inf); vocabulary masking with -inf
  *     is not part of the policy the paper defines (App. C).
