@@ -237,7 +237,7 @@ aero_status aero_grpo_loss_bwd_noalloc(
  * hidden   bf16 [T, H] row-major, weight bf16 [V, H] row-major, both 16-byte aligned, H % 8 == 0.
  * Forward outputs  logprob[T], lse[T] f32, entropy[T] f32 or NULL.
  * Backward part (old_logprob .. dweight; pass old_logprob == NULL for forward only):
- *   loss f32[1]; dhidden bf16 [T, H] = dz @ weight; dweight [V, H] = dz^T @ hidden in
+ *   loss f32[1]; dhidden bf16 [T, H] (16-byte aligned) = dz @ weight; dweight [V, H] = dz^T @ hidden in
  *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd
  *   (entropy_coef and kl_coef / ref_logprob included: the entropy of the forward part is used,
  *   also when the `entropy` output is NULL).

@@ -130,33 +130,42 @@ __global__ __launch_bounds__(1024) void k_compact_valid(
     const int32_t* __restrict__ targets, int64_t T, int64_t T_pad, int V, int32_t* __restrict__ fidx,
     int32_t* __restrict__ nf, float* __restrict__ logprob, float* __restrict__ entropy, float* __restrict__ lse_out,
     int32_t* __restrict__ err_flag) {
-  __shared__ int part[1024];
-  const int tid = threadIdx.x;
-  const int64_t per = (T + 1023) / 1024;
-  const int64_t lo = min(T, tid * per), hi = min(T, lo + per);
+  // each of the 16 waves owns one contiguous range of rows and walks it 64 rows at a time (coalesced
+  // reads, ballot + popcount inside the wave): count, exchange the 16 counts, then place
+  __shared__ int wsum[16];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int64_t seg = ((T + 15) / 16 + 63) / 64 * 64;
+  const int64_t lo = min(T, wave * seg), hi = min(T, lo + seg);
+  const uint64_t below = (uint64_t(1) << lane) - 1;
   int cnt = 0;
-  for (int64_t t = lo; t < hi; ++t) cnt += unsigned(targets[t]) < unsigned(V);
-  part[tid] = cnt;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const int v = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  for (int64_t t0 = lo; t0 < hi; t0 += 64) {
+    const int64_t t = t0 + lane;
+    cnt += __popcll(__ballot(t < hi && unsigned(targets[t < hi ? t : lo]) < unsigned(V)));
   }
-  int run = tid ? part[tid - 1] : 0;
-  const int total = part[1023];
+  if (lane == 0) wsum[wave] = cnt;
+  __syncthreads();
+  int run = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    run += w < wave ? wsum[w] : 0;
+    total += wsum[w];
+  }
   bool bad = false;
-  for (int64_t t = lo; t < hi; ++t) {
-    const int y = targets[t];
-    if (unsigned(y) < unsigned(V)) {
-      fidx[run++] = int(t);
-    } else {
+  for (int64_t t0 = lo; t0 < hi; t0 += 64) {
+    const int64_t t = t0 + lane;
+    const bool in = t < hi;
+    const int y = in ? targets[t] : -1;
+    const bool ok = in && unsigned(y) < unsigned(V);
+    const uint64_t m = __ballot(ok);
+    if (ok) {
+      fidx[run + __popcll(m & below)] = int(t);
+    } else if (in) {
       logprob[t] = 0.f;
       lse_out[t] = 0.f;
       if (entropy) entropy[t] = 0.f;
       bad |= y >= V;
     }
+    run += __popcll(m);
   }
   if (bad && err_flag) atomicOr(err_flag, AERO_DERR_BAD_TARGET);
   for (int64_t j = total + tid; j < T_pad; j += 1024) fidx[j] = -1;
@@ -313,36 +322,44 @@ __global__ __launch_bounds__(1024) void k_compact_tokens(
     int64_t T_pad, int32_t* __restrict__ idx, int32_t* __restrict__ pos, int32_t* __restrict__ nact,
     float* __restrict__ gc, float* __restrict__ lsec, int32_t* __restrict__ yc, float* __restrict__ ac,
     float* __restrict__ bc) {
-  __shared__ int part[1024];
-  const int tid = threadIdx.x;
-  const int64_t per = (T + 1023) / 1024;
-  const int64_t lo = min(T, tid * per), hi = min(T, lo + per);
+  // as k_compact_valid: one contiguous range of tokens per wave, 64 at a time
+  __shared__ int wsum[16];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int64_t seg = ((T + 15) / 16 + 63) / 64 * 64;
+  const int64_t lo = min(T, wave * seg), hi = min(T, lo + seg);
+  const uint64_t below = (uint64_t(1) << lane) - 1;
   auto active = [&](int64_t t) -> bool { return g[t] != 0.f || (ea && ea[t] != 0.f); };
   int cnt = 0;
-  for (int64_t t = lo; t < hi; ++t) cnt += active(t);
-  part[tid] = cnt;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const int v = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  for (int64_t t0 = lo; t0 < hi; t0 += 64) {
+    const int64_t t = t0 + lane;
+    cnt += __popcll(__ballot(t < hi && active(t < hi ? t : lo)));
   }
-  int run = tid ? part[tid - 1] : 0;
-  const int total = part[1023];
-  for (int64_t t = lo; t < hi; ++t) {
-    if (active(t)) {
-      idx[run] = int(t);
-      pos[t] = run;
-      gc[run] = g[t];
-      lsec[run] = lse[t];
-      yc[run] = targets[t];
-      ac[run] = ea ? ea[t] : 0.f;
-      bc[run] = ea ? eb[t] : -g[t];
-      ++run;
-    } else {
+  if (lane == 0) wsum[wave] = cnt;
+  __syncthreads();
+  int run = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    run += w < wave ? wsum[w] : 0;
+    total += wsum[w];
+  }
+  for (int64_t t0 = lo; t0 < hi; t0 += 64) {
+    const int64_t t = t0 + lane;
+    const bool in = t < hi;
+    const bool act = in && active(t);
+    const uint64_t m = __ballot(act);
+    if (act) {
+      const int r = run + __popcll(m & below);
+      idx[r] = int(t);
+      pos[t] = r;
+      gc[r] = g[t];
+      lsec[r] = lse[t];
+      yc[r] = targets[t];
+      ac[r] = ea ? ea[t] : 0.f;
+      bc[r] = ea ? eb[t] : -g[t];
+    } else if (in) {
       pos[t] = -1;
     }
+    run += __popcll(m);
   }
   for (int64_t j = total + tid; j < T_pad; j += 1024) {   // padding entries: no gradient
     idx[j] = -1;
@@ -698,17 +715,31 @@ __global__ __launch_bounds__(256) void k_scatter_dh(const float* __restrict__ dh
                                                     uint16_t* __restrict__ dhidden) {
   const int64_t t = blockIdx.x;
   const int j = pos[t];
-  uint16_t* out = dhidden + t * H;
+  uint16_t* out = dhidden + t * H;   // H % 8 == 0 and a 16-byte aligned base: rows are whole 16-byte vectors
   if (j < 0) {
-    for (int k = threadIdx.x; k < H; k += 256) out[k] = 0;
+    for (int k = threadIdx.x * 8; k < H; k += 256 * 8) *reinterpret_cast<u32x4_t*>(out + k) = u32x4_t{0u, 0u, 0u, 0u};
     return;
   }
   const int n_pad = nact[1];
   const int S = dh_splits(n_pad / kTile, tiles_h, dh_grid, slices, rows_max);   // as the contraction chose it
-  for (int k = threadIdx.x; k < H; k += 256) {
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc += dh_part[(int64_t(s) * n_pad + j) * H + k];
-    out[k] = f32_to_bf16(acc);
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  for (int k = threadIdx.x * 4; k < H; k += 256 * 4) {
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const float* src = dh_part + int64_t(j) * H + k;
+    const int64_t step = int64_t(n_pad) * H;
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {   // four loads in flight, added in split order
+      f32x4_t v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(src + (s + u) * step));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc += v[u];
+    }
+    for (; s < S; ++s) acc += __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(src + s * step));
+    uint2 o;
+    o.x = pack_bf16x2(acc.x, acc.y);
+    o.y = pack_bf16x2(acc.z, acc.w);
+    *reinterpret_cast<uint2*>(out + k) = o;
   }
 }
 
@@ -741,6 +772,7 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   if (bwd && (!loss || !dweight || (T > 0 && (!token_rollout || !adv || !weight_rollout || !dhidden))))
     return AERO_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(hidden) % 16 || reinterpret_cast<uintptr_t>(weight) % 16) return AERO_ERR_ALIGN;
+  if (bwd && reinterpret_cast<uintptr_t>(dhidden) % 16) return AERO_ERR_ALIGN;   // rows are written as 16-byte vectors
   const FusedPlan p = make_plan(T, V, H);
   // operands are addressed with 32-bit byte offsets: every slab operand must stay below 4 GiB
   constexpr size_t kOperandLimit = size_t(1) << 32;

@@ -218,4 +218,16 @@ def test_fused_host_side_argument_errors(gh):
         aero.aero_lmhead_logprob_fused(h_ok, w, T, 60, V, tg, lp, ent, lse, workspace=ws)       # H % 8 != 0
     with pytest.raises(aero.AeroError, match="NULL"):
         aero.aero_lmhead_logprob_fused(h_ok, w, T, H, V, None, lp, ent, lse, workspace=ws)
+    # backward part: a dhidden that does not start on a 16-byte boundary
+    R = 4
+    old, adv, wr = torch.zeros(T, device=dev), torch.ones(R, device=dev), torch.ones(R, device=dev)
+    tr = torch.zeros(T, dtype=torch.int32, device=dev)
+    loss = torch.zeros(1, device=dev)
+    dw = torch.zeros((V, H), device=dev)
+    dflat = torch.zeros(T * H + 8, dtype=torch.bfloat16, device=dev)
+    with pytest.raises(aero.AeroError, match="pointer or leading dimension"):
+        aero.aero_lmhead_logprob_fused(h_ok, w, T, H, V, tg, lp, ent, lse, old, tr, adv, wr, R, loss=loss,
+                                       dhidden=dflat[1:T * H + 1].view(T, H), dweight=dw, workspace=ws)
+    aero.aero_lmhead_logprob_fused(h_ok, w, T, H, V, tg, lp, ent, lse, old, tr, adv, wr, R, loss=loss,
+                                   dhidden=dflat[:T * H].view(T, H), dweight=dw, workspace=ws)
     torch.cuda.synchronize()
