@@ -87,6 +87,28 @@ def test_group_advantage_edge_cases(gh):
                       rng.integers(0, 2 ** 32, size=R, dtype=np.uint32)), dict(reject_enable=1, posterior_mode=1))
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_group_advantage_random_structures(gh, seed):
+    """Seeded random group structures (empty, single, several strides of 64 wide), success rates, tied keys
+    and hyper-parameters of the curation step, all outputs bit for bit / to 1e-6 against the checker."""
+    rng = np.random.default_rng(1000 + seed)
+    Q = int(rng.integers(1, 300))
+    sizes = np.where(rng.random(Q) < 0.1, rng.integers(65, 200, size=Q), rng.integers(0, 34, size=Q))
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(off[-1])
+    p_q = np.repeat(rng.beta(0.5, 0.5, size=Q), sizes)
+    rewards = (rng.random(R) < p_q).astype(np.float32)
+    lengths = rng.integers(1, 3000, size=R).astype(np.int32)
+    keys = rng.integers(0, int(rng.choice([2, 5, 2 ** 32])), size=R).astype(np.uint32)
+    tau = [(1, 2), (1, 3), (2, 3), (1, 1)][int(rng.integers(4))]
+    params = dict(k_ratio=int(rng.integers(1, 5)), s_rescue=int(rng.integers(0, 4)), tau_num=tau[0], tau_den=tau[1],
+                  zero_keep=int(rng.integers(1, 7)), reject_enable=int(rng.integers(2)),
+                  posterior_mode=int(rng.integers(2)), alpha0=float(rng.choice([0.5, 1.0, 2.0])),
+                  beta0=float(rng.choice([0.5, 1.0, 3.0])))
+    check_groups(gh, (rewards, lengths, off, keys), params)
+    check_groups(gh, (rewards, lengths, off, keys), params, keys=None)
+
+
 def test_group_advantage_general_rewards_and_error_flag(gh):
     rng = np.random.default_rng(22)
     sizes = [5, 9, 16, 70]
@@ -442,6 +464,31 @@ def test_f8_gradient_rounding_bit_exact(gh):
         assert np.array_equal(got[:, 1], want)            # g (1 - p_1) = x
         assert np.array_equal(got[:, 0], want ^ 0x80)     # g (0 - p_0) = -x
         assert not (got[:, 2:] & 0x7F).any()              # -x * 0: a zero of either sign
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_all_storage_types(gh, seed):
+    """Seeded random vocabulary sizes, row pitches (aligned and not), batch shapes, storage types and call
+    variants: statistics, loss and gradient against the checker as in the fixed cases."""
+    rng = np.random.default_rng(2000 + seed)
+    dtype = ["bf16", "f32", "f16", "f8e4m3"][seed % 4]
+    V = int(rng.choice([rng.integers(1, 64), rng.integers(64, 3000), rng.integers(3000, 40000)]))
+    ld = V + int(rng.choice([0, 0, rng.integers(1, 40)]))
+    slots = int(rng.integers(3, 13))
+
+    def wl():
+        return ai.make_config("cfg2", seed=100 + seed, V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots - 1, dtype=dtype)
+    active = (wl().token_rollout >= 0).astype(np.uint8)
+    assert check_fwd(gh, wl()) == 0
+    assert check_fwd(gh, wl(), row_active=active, offset_elems=int(rng.integers(0, 9))) == 0
+    gs = {"f16": 4096.0, "f8e4m3": 256.0}.get(dtype, float(rng.choice([1.0, 3.0])))
+    for _ in range(3):
+        terms = rng.random() < 0.4
+        check_loss_bwd(gh, wl(), dict(reject_enable=int(rng.integers(2)), posterior_mode=int(rng.integers(2))),
+                       sigma_old=float(rng.choice([0.05, 0.3])), use_oracle_lse=bool(rng.integers(2)),
+                       inplace=bool(rng.integers(2)), grad_scale=gs, stats=False,
+                       entropy_coef=0.01 if terms else 0.0, kl_coef=0.04 if terms and rng.random() < 0.5 else 0.0,
+                       untouched=[None, "half", "all"][int(rng.integers(3))])
 
 
 def test_loss_bwd_cfg3_reduced(gh):
