@@ -131,6 +131,34 @@ def test_fused_backward(gh, T, H, V):
     check_bwd(gh, wl, h, W, dict(reject_enable=1, posterior_mode=1), dweight_dtype=torch.bfloat16, grad_scale=8.0)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_fused_random_shapes(gh, seed):
+    """Seeded random token counts, hidden sizes (multiples of 8, with and without whole 64-wide K slices)
+    and vocabulary sizes (ragged last tile), both workload kinds, random call variants."""
+    rng = np.random.default_rng(3000 + seed)
+    T = int(rng.choice([rng.integers(1, 40), rng.integers(40, 600), rng.integers(600, 1500)]))
+    H = 8 * int(rng.choice([rng.integers(1, 9), rng.integers(9, 80)]))
+    V = int(rng.choice([rng.integers(2, 300), rng.integers(300, 6000)]))
+    name = ["cfg4", "cfg5"][seed % 2]
+    wl, h, W = make(T, H, V, Q=int(rng.integers(2, 12)), sigma_w=2.0 / np.sqrt(H), name=name, seed=50 + seed,
+                    len_hi=max(2, T // int(rng.integers(2, 9))))
+    tg = wl.targets.copy()
+    if T > 8:
+        tg[rng.integers(0, T, size=3)] = -1          # rows without a target take no part
+    ref = orc.lmhead_fused(h, W, tg)
+    out = run_fused(gh, wl, h, W, tg)
+    assert out["err"] == 0
+    for k in ("logprob", "entropy", "lse"):
+        got = out[k].cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref[k]).max() <= 2e-3 and not got[tg < 0].any(), k
+    terms = rng.random() < 0.5
+    check_bwd(gh, wl, h, W, dict(reject_enable=int(rng.integers(2)), posterior_mode=int(rng.integers(2))),
+              sigma_old=float(rng.choice([0.05, 0.3])),
+              dweight_dtype=[torch.float32, torch.bfloat16][int(rng.integers(2))],
+              grad_scale=float(rng.choice([1.0, 8.0])), entropy_coef=0.01 if terms else 0.0,
+              kl_coef=0.04 if terms and rng.random() < 0.5 else 0.0)
+
+
 def test_fused_backward_several_chunks_and_recipe_scale(gh):
     """Vocabulary wider than one backward chunk at this T (2 x 24576 > chunk), paper-scale weights."""
     wl, h, W = make(2816, 128, 40000, Q=8, len_hi=500)
