@@ -7,6 +7,9 @@
 //   k_group     per group: c, category, keep mask, advantages, weights, kept count
 //   k_scan      one workgroup: exclusive scan of the kept counts -> kept_offsets
 //   k_compact   per group: kept rollout indices, ascending, written at kept_offsets[q]
+// or, for the usual small problem (a micro-batch or a step's worth of groups), the same three
+// stages in one workgroup and one launch (k_group_small): the call is latency bound, and two
+// launches less are two thirds of its time.
 #include "aero_device.h"
 
 namespace aero {
@@ -39,15 +42,13 @@ __device__ __forceinline__ bool before(uint32_t ka, int ia, uint32_t kb, int ib)
 
 constexpr int kGroupsPerBlock = 4;   // 4 waves of 64
 
-__global__ __launch_bounds__(kGroupsPerBlock* kWave) void k_group(
-    const float* __restrict__ rewards, const int32_t* __restrict__ lengths,
+// One group, one wave: everything but the position of its kept rollouts in kept_index.  Returns the
+// number of kept rollouts (the same value in every lane).
+__device__ __forceinline__ int group_body(
+    int q, int lane, const float* __restrict__ rewards, const int32_t* __restrict__ lengths,
     const int32_t* __restrict__ group_offsets, const uint32_t* __restrict__ keys, int Q, int R,
-    aero_adv_params p, float* __restrict__ adv, float* __restrict__ weight, uint8_t* __restrict__ keep_mask,
-    int32_t* __restrict__ kept_offsets, uint8_t* __restrict__ zero_var, uint8_t* __restrict__ category,
-    int32_t* __restrict__ err_flag) {
-  const int lane = threadIdx.x % kWave;
-  const int q = blockIdx.x * kGroupsPerBlock + threadIdx.x / kWave;
-  if (q >= Q) return;   // whole wave leaves together
+    const aero_adv_params& p, float* __restrict__ adv, float* __restrict__ weight, uint8_t* __restrict__ keep_mask,
+    uint8_t* __restrict__ zero_var, uint8_t* __restrict__ category, int32_t* __restrict__ err_flag) {
   int b = group_offsets[q], e = group_offsets[q + 1];
   b = max(0, min(b, R));   // offsets outside [0, R] cannot make the kernel read out of bounds
   e = max(b, min(e, R));
@@ -145,10 +146,40 @@ __global__ __launch_bounds__(kGroupsPerBlock* kWave) void k_group(
     weight[i] = w;
   }
   if (lane == 0) {
-    kept_offsets[q + 1] = nk;
     zero_var[q] = zv ? 1 : 0;
     category[q] = uint8_t(cat | (c <= p.s_rescue ? AERO_CAT_RESCUE_BIT : 0));
   }
+  return nk;
+}
+
+// Kept rollout indices of one group, ascending, written from position `out` on (one wave).
+__device__ __forceinline__ void compact_body(int q, int lane, const int32_t* __restrict__ group_offsets,
+                                             const uint8_t* __restrict__ keep_mask, int out, int R,
+                                             int32_t* __restrict__ kept_index) {
+  int b = group_offsets[q], e = group_offsets[q + 1];
+  b = max(0, min(b, R));
+  e = max(b, min(e, R));
+  for (int base = b; base < e; base += kWave) {   // trip count is uniform over the wave
+    const int i = base + lane;
+    const bool k = i < e && keep_mask[i] != 0;
+    const uint64_t bal = __ballot(k);
+    if (k) kept_index[out + __popcll(bal & ((uint64_t(1) << lane) - 1))] = i;
+    out += __popcll(bal);
+  }
+}
+
+__global__ __launch_bounds__(kGroupsPerBlock* kWave) void k_group(
+    const float* __restrict__ rewards, const int32_t* __restrict__ lengths,
+    const int32_t* __restrict__ group_offsets, const uint32_t* __restrict__ keys, int Q, int R,
+    aero_adv_params p, float* __restrict__ adv, float* __restrict__ weight, uint8_t* __restrict__ keep_mask,
+    int32_t* __restrict__ kept_offsets, uint8_t* __restrict__ zero_var, uint8_t* __restrict__ category,
+    int32_t* __restrict__ err_flag) {
+  const int lane = threadIdx.x % kWave;
+  const int q = blockIdx.x * kGroupsPerBlock + threadIdx.x / kWave;
+  if (q >= Q) return;   // whole wave leaves together
+  const int nk = group_body(q, lane, rewards, lengths, group_offsets, keys, Q, R, p, adv, weight, keep_mask, zero_var,
+                            category, err_flag);
+  if (lane == 0) kept_offsets[q + 1] = nk;
 }
 
 // Exclusive scan of counts held in kept_offsets[1..Q] (in place), kept_offsets[0] = 0.
@@ -181,17 +212,52 @@ __global__ __launch_bounds__(kGroupsPerBlock* kWave) void k_compact(
   const int lane = threadIdx.x % kWave;
   const int q = blockIdx.x * kGroupsPerBlock + threadIdx.x / kWave;
   if (q >= Q) return;
-  int b = group_offsets[q], e = group_offsets[q + 1];
-  b = max(0, min(b, R));
-  e = max(b, min(e, R));
-  int out = kept_offsets[q];
-  for (int base = b; base < e; base += kWave) {   // trip count is uniform over the wave
-    const int i = base + lane;
-    const bool k = i < e && keep_mask[i] != 0;
-    const uint64_t bal = __ballot(k);
-    if (k) kept_index[out + __popcll(bal & ((uint64_t(1) << lane) - 1))] = i;
-    out += __popcll(bal);
+  compact_body(q, lane, group_offsets, keep_mask, kept_offsets[q], R, kept_index);
+}
+
+// The three stages in one workgroup of 16 waves, for Q <= kSmallQ groups: wave w takes groups w, w + 16, ...;
+// the kept counts and their scan stay in LDS; every wave then places the kept indices of the groups it
+// processed (it reads back the keep mask its own lanes wrote).
+constexpr int kSmallQ = 2048, kSmallR = 1 << 16, kSmallNT = 1024;
+__global__ __launch_bounds__(kSmallNT) void k_group_small(
+    const float* __restrict__ rewards, const int32_t* __restrict__ lengths,
+    const int32_t* __restrict__ group_offsets, const uint32_t* __restrict__ keys, int Q, int R,
+    aero_adv_params p, float* __restrict__ adv, float* __restrict__ weight, uint8_t* __restrict__ keep_mask,
+    int32_t* __restrict__ kept_index, int32_t* __restrict__ kept_offsets, uint8_t* __restrict__ zero_var,
+    uint8_t* __restrict__ category, int32_t* __restrict__ err_flag) {
+  __shared__ int start[kSmallQ + 1];   // counts, then exclusive offsets
+  __shared__ int part[kSmallNT / kWave];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  constexpr int kWaves = kSmallNT / kWave;
+  for (int q = wave; q < Q; q += kWaves) {
+    const int nk = group_body(q, lane, rewards, lengths, group_offsets, keys, Q, R, p, adv, weight, keep_mask, zero_var,
+                              category, err_flag);
+    if (lane == 0) start[q] = nk;
   }
+  __syncthreads();
+  // exclusive scan of start[0 .. Q): two entries per thread, shuffles inside a wave, the 16 wave totals through LDS
+  const int q0 = 2 * tid, q1 = 2 * tid + 1;
+  const int c0 = q0 < Q ? start[q0] : 0, c1 = q1 < Q ? start[q1] : 0;
+  int incl = c0 + c1;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int v = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += v;
+  }
+  if (lane == kWave - 1) part[wave] = incl;
+  __syncthreads();   // also: every read of start[] above precedes the writes below
+  int before_me = incl - (c0 + c1), total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    before_me += w < wave ? part[w] : 0;
+    total += part[w];
+  }
+  if (q0 < Q) start[q0] = before_me;
+  if (q1 < Q) start[q1] = before_me + c0;
+  if (tid == 0) start[Q] = total;
+  __syncthreads();
+  for (int q = tid; q <= Q; q += kSmallNT) kept_offsets[q] = start[q];
+  for (int q = wave; q < Q; q += kWaves) compact_body(q, lane, group_offsets, keep_mask, start[q], R, kept_index);
 }
 
 }  // namespace aero
@@ -208,6 +274,11 @@ extern "C" aero_status aero_group_advantage(
   if (Q > 0 && (!group_zero_var || !group_category)) return AERO_ERR_NULL;
   if (R > 0 && (!rewards || !lengths || !adv || !weight || !keep_mask || !kept_index)) return AERO_ERR_NULL;
   hipStream_t s = as_stream(stream);
+  if (Q > 0 && Q <= kSmallQ && R <= kSmallR) {
+    hipLaunchKernelGGL(k_group_small, dim3(1), dim3(kSmallNT), 0, s, rewards, lengths, group_offsets, keep_priority, Q, R,
+                       *p, adv, weight, keep_mask, kept_index, kept_offsets, group_zero_var, group_category, err_flag);
+    return launch_status();
+  }
   const unsigned blocks = unsigned((Q + kGroupsPerBlock - 1) / kGroupsPerBlock);
   if (Q > 0)
     hipLaunchKernelGGL(k_group, dim3(blocks), dim3(kGroupsPerBlock * kWave), 0, s, rewards, lengths, group_offsets,
