@@ -36,8 +36,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 # see profiles/logits_path_cfg2_hbm_traffic.txt).  Not a measurement of this run: a figure from
 # that profile, valid only for the kernel sources it was taken on, so it is reported only while
 # their hash still matches and is null otherwise.
-MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8594e+09, "sources_sha256": "1f2a664388fee4d691d3d6e51fbeb08ae412c7b4a1b1344dbcf40e44b350189a"},
-                    "cfg2-untouched": {"bytes": 5.7482e+09, "sources_sha256": "1f2a664388fee4d691d3d6e51fbeb08ae412c7b4a1b1344dbcf40e44b350189a"}}
+MEASURED_TRAFFIC = {"cfg2": {"bytes": 7.8592e+09, "sources_sha256": "1f2a664388fee4d691d3d6e51fbeb08ae412c7b4a1b1344dbcf40e44b350189a"},
+                    "cfg2-untouched": {"bytes": 5.7484e+09, "sources_sha256": "1f2a664388fee4d691d3d6e51fbeb08ae412c7b4a1b1344dbcf40e44b350189a"}}
 TRAFFIC_SOURCES = ("paper_2602_14338_amd/csrc/grpo_single_pass.hip", "paper_2602_14338_amd/csrc/aero_device.h")
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of the same kernel sources "
                 "(profiles/logits_path_cfg2_hbm_traffic.txt), not of this run; null once the sources changed")
