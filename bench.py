@@ -616,6 +616,10 @@ def run_fused(args, name, mods):
     n_grad = int(round(signal * (1.0 - clip.item())))
     flops = 2.0 * wl.n_valid * V * H + 6.0 * n_grad * V * H
     tf = flops / (ms_fused * 1e-3) / 1e12
+    # what the kernels execute: the backward pass reuses the exponentials the forward pass stored for the rows
+    # that may carry gradient (signal rows) instead of forming their logits again, so its contractions are two
+    flops_exec = 2.0 * wl.n_valid * V * H + 4.0 * signal * V * H
+    tf_exec = flops_exec / (ms_fused * 1e-3) / 1e12
     tf_fwd = 2.0 * wl.n_valid * V * H / (ms_fwd * 1e-3) / 1e12
     out = {
         "metric": "tokens/s, fused LM-head GRPO logprob+loss fwd/bwd at V=%d, H=%d" % (V, H),
@@ -630,7 +634,15 @@ def run_fused(args, name, mods):
         "roofline": {"kernel": "whole aero_lmhead_logprob_fused call (fwd + bwd; median of %d calls), algorithmic flops "
                                "2 T_valid V H + 6 T_grad V H" % K, "bound": "mfma", "achieved": tf,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
-                     "algorithmic_flops": flops, "traffic": None},
+                     "algorithmic_flops": flops,
+                     "accounting": "forward on every row with a target (2 V H per row) + recompute, dhidden and dweight "
+                                   "on the rows with gradient (6 V H per row): the method's count, whatever the kernels do",
+                     "executed": {"flops": flops_exec, "achieved": tf_exec, "frac": tf_exec / MFMA_BF16_PEAK_TFLOPS,
+                                  "accounting": "2 V H per row with a target + 4 V H per signal row: the logits of the "
+                                                "gradient rows are not formed a second time (the forward pass leaves "
+                                                "exp(z - z_y) for them), so the recompute term is credited above but "
+                                                "not executed"},
+                     "traffic": None},
         "roofline_fwd": {"kernel": "fused forward call (gather + k_fused_stats + combine), 2 T_valid V H", "bound": "mfma",
                          "achieved": tf_fwd, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": tf_fwd / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
