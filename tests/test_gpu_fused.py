@@ -227,6 +227,33 @@ def test_fused_all_groups_zero_variance(gh):
     assert not out["dhidden"].view(torch.int16).any() and not out["dweight"].any()
 
 
+def test_fused_rows_outside_every_rollout(gh):
+    """Token rows with a target but no usable rollout (padding index, untouched mark, index past R): their
+    statistics are still computed, they take no part in the gradient contractions, their dhidden rows are +0,
+    and only the index past R raises the device error bit; the other rows match the checker."""
+    from paper_2602_14338_amd import binding
+    wl, h, W = make(520, 128, 1000, sigma_w=0.3)
+    tr = wl.token_rollout.copy()
+    tr[5], tr[6], tr[300] = -1, binding.AERO_ROW_UNTOUCHED, wl.R + 3
+    tr_ref = tr.copy()
+    tr_ref[[5, 6, 300]] = -1
+    ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams())
+    a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+    fwd = orc.lmhead_fused(h, W, wl.targets)
+    old = ai.draw_old_logprob(fwd["logprob"], wl.seed, sigma=0.3)
+    ref = orc.lmhead_fused(h, W, wl.targets, old, tr_ref, a32, w32, np.float32(0.2), np.float32(0.2), 1.0)
+    wl.token_rollout = tr
+    out = run_fused(gh, wl, h, W, wl.targets, bwd=dict(old=old, adv=a32, weight=w32))
+    assert out["err"] == 4                      # AERO_DERR_BAD_ROLLOUT
+    gh.assert_loss(out["loss"].item(), ref["loss"], ref["loss_terms"])
+    for k in ("logprob", "entropy", "lse"):
+        assert np.abs(out[k].cpu().numpy().astype(np.float64) - fwd[k]).max() <= 2e-3, k
+    dh = out["dhidden"].float().cpu().numpy().astype(np.float64)
+    dw = out["dweight"].float().cpu().numpy().astype(np.float64)
+    assert rowwise_close(dh, ref["dhidden"]) and rowwise_close(dw, ref["dweight"])
+    assert not out["dhidden"].view(torch.int16)[[5, 6, 300]].any()
+
+
 def test_fused_matches_logits_path(gh):
     """Same inputs through the materialised-logits kernels: both routes agree with each other
     as closely as each agrees with the checker."""
