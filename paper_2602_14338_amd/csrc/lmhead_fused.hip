@@ -53,7 +53,7 @@ struct FusedPlan {
 };
 
 // dhidden is formed as S split-K partials of the active rows, S chosen on the device so that
-// (active token tiles) x (H tiles) x S fills the launch grid in whole rounds; the buffer holds S
+// (candidate token tiles) x (H tiles) x S fills the launch grid in whole rounds; the buffer holds S
 // stacked copies of the active rows, never more rows than the launch grid covers.  A split's
 // operands are addressed with 32-bit byte offsets, so a split may span at most 4 GiB of the dz
 // slabs: the grid leaves room for that many splits (plus one) when every token is active.
@@ -680,7 +680,7 @@ __global__ __launch_bounds__(256) void k_gather_transpose_vec(
 // the two K-slab layouts the next two contractions read: dz as [v / 64][token][64] (K = vocab)
 // and dzT as [v / VC][token / 64][v % VC][64] (K = tokens, in vocabulary chunks of VC rows so that
 // one chunk stays below the 4 GiB a buffer descriptor can address); entries outside the
-// vocabulary or the active tokens are zero.
+// vocabulary or the candidate tokens are zero.
 // ENT: rows also carry the entropy-bonus term, dz = pi (ac z + bc) + gc onehot; otherwise ac = 0
 // and the scale is the per-token constant bc = -g.
 // The kernel is the recompute mode of the backward pass (see k_candidate_scalars): with force == 0 it
@@ -694,7 +694,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
     uint16_t* __restrict__ dzT) {
   extern __shared__ __align__(16) uint16_t smem[];
   if (!force && nact[2] == 0) return;   // uniform over the launch
-  // tile order over the active token tiles only (see k_fused_stats)
+  // tile order over the candidates' token tiles only (see k_fused_stats)
   const int tiles_t_act = nact[1] / kTile;
   int tv, tt;
   if (!tile_of_block(tiles_v, tiles_t_act, 0, tiles_v * tiles_t_act, tv, tt)) return;
@@ -755,7 +755,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_fused_dz(
 // ------------------------------------------------------------------------------------------
 // backward: the two gradient GEMMs
 // ------------------------------------------------------------------------------------------
-// Split-K factor for dhidden, from the number of active token tiles (uniform, device side).
+// Split-K factor for dhidden, from the number of candidate token tiles (uniform, device side).
 // A workgroup's time is its share of the K slices plus a fixed tail (storing its fp32 partial
 // tile, worth about 8 slices of main loop); the launch takes ceil(workgroups / 256) such rounds.
 // S minimises rounds x (slices / S + 8) among the S whose splits stay addressable: a split's
@@ -779,7 +779,8 @@ __device__ __forceinline__ int dh_splits(int active_tiles, int tiles_h, int grid
   return best;
 }
 
-// dh_part[s][t][h] = sum_{k in split s} dz[t][k] W[k][h]     M = active tokens, N = H, K = vocabulary (padded)
+// dh_part[s][t][h] = sum_{k in split s} X[t][k] W[k][h], X = the stored exponentials P (or dz itself on the recompute
+// route)     M = candidate tokens, N = H, K = vocabulary (padded)
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
     const uint16_t* __restrict__ dz, const uint16_t* __restrict__ WT, int H_pad, int vK,
     int H, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact, float* __restrict__ dh_part) {
@@ -820,7 +821,7 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dh(
   }
 }
 
-// dW[m][h] = sum_t dzT[m][t] hTc[h][t]          M = V, N = H, K = active tokens (padded)
+// dW[m][h] = sum_t XT[m][t] hTc[h][t], hTc = the candidates' hidden rows times their scale     M = V, N = H, K = candidate tokens (padded)
 template <bool OUT_BF16>
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
     const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int VC, int H_pad, int V, int H,
