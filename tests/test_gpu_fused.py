@@ -3,8 +3,8 @@ the gradients w.r.t. hidden states and LM-head weight, against the float64 check
 forms the logits as a float64 product and then applies the logits-path definitions).
 
 Tolerances: log-prob / entropy / lse 2e-3 absolute; loss 1e-4 relative (plus an fp32 rounding floor only where the terms cancel, see gpu_helpers.loss_bound); gradients are checked
-scale-free, per row, against 1e-2 of the largest reference entry of that row (dz is rounded
-to bf16 before it enters the two gradient contractions, dhidden is stored in bf16)."""
+scale-free, per row, against 1e-2 of the largest reference entry of that row (the operands of
+the two gradient contractions are rounded to bf16, dhidden is stored in bf16)."""
 import numpy as np
 import pytest
 import torch
