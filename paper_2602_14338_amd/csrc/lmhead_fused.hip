@@ -19,7 +19,7 @@
 //                            scale travels with the other operand (dweight) or is applied after the
 //                            contraction (dhidden), so z is never formed a second time
 //           k_fused_dz       only when that does not apply (an entropy term in the rows, or a sampled
-//                            token more than 64 nats below another logit, where P would leave its safe
+//                            token more than 40 nats below another logit, where P would leave its safe
 //                            range): recompute the z^T tile and store dz itself in the same layouts
 //           k_gemm_dh        dhidden partials = (P or dz) @ weight   (split-K over the vocabulary, fp32)
 //           k_gemm_dw        dweight = (P or dz)^T @ (scale * hidden)
@@ -330,11 +330,13 @@ __device__ __forceinline__ void store_tile_both_layouts(const uint32_t (&pk)[kNB
 //   dz[t, v] = s_t P[t, v] (v != y_t),  s_t = -g_t exp(logprob_t),  because exp(z - lse) = exp(z - zy) exp(zy - lse);
 // the per-token factor s_t moves into the other operand (dweight) or behind the contraction (dhidden), and the
 // one entry per row that differs, v = y_t, is overwritten once the log-prob is known (k_candidate_scalars).
-// bf16 keeps fp32's exponent range, so P is safe as long as z - zy stays far below 88; a tile that sees
+// bf16 keeps fp32's exponent range, so P is safe as long as z - zy stays far below 88, and so is the scale
+// (about g times the sampled token's probability, which must stay a normal number after it is multiplied
+// into a bf16 hidden row) as long as that probability is not below e^-52 or so; a tile that sees
 // z - zy > kStoreRange on a candidate column raises nact[2], and the backward pass then forms dz by
 // recomputing z as it does for rows with an entropy term (k_fused_dz).  The exponentials are the ones the
 // statistics take anyway: P = exp(z - m) * exp(m - zy) with m the running offset of the lane.
-constexpr float kStoreRange = 64.f;
+constexpr float kStoreRange = 40.f;
 
 // stat_update for 16 values that also hands back the exponentials it formed (relative to st.m on return)
 // and the largest of the 16 values.

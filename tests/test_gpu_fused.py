@@ -159,17 +159,17 @@ def test_fused_random_shapes(gh, seed):
               kl_coef=0.04 if terms and rng.random() < 0.5 else 0.0)
 
 
-@pytest.mark.parametrize("z_std", [8.0, 25.0])
+@pytest.mark.parametrize("z_std", [5.0, 25.0])
 def test_fused_backward_wide_logits(gh, z_std):
-    """Logits spread so widely that sampled tokens lie tens of nats (z_std = 8) or more than the stored
-    exponentials' safe range (z_std = 25: up to a hundred nats) below the row maximum.  The first stays on the
+    """Logits spread so widely that sampled tokens lie tens of nats (z_std = 5: up to 33) or more than the stored
+    exponentials' safe range of 40 (z_std = 25: up to 165) below the row maximum.  The first stays on the
     route that reuses the forward pass's exponentials, the second makes the forward pass raise its flag and the
     backward pass recompute the logits; both must match the checker."""
     T, H, V = 520, 128, 3000
     wl, h, W = make(T, H, V, sigma_w=z_std / np.sqrt(H))
     z = orc.lmhead_logits(h, W)
     gap = z.max(axis=1) - z[np.arange(T), wl.targets]
-    assert (gap.max() > 64.0) == (z_std > 20.0) and gap.max() > 20.0
+    assert (gap.max() > 40.0) == (z_std > 20.0) and gap.max() > 30.0
     check_bwd(gh, wl, h, W, dict())
     check_bwd(gh, wl, h, W, dict(reject_enable=1, posterior_mode=1), dweight_dtype=torch.bfloat16, grad_scale=8.0,
               kl_coef=0.04)
