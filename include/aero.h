@@ -58,6 +58,11 @@ enum {
  * more.  All arithmetic is fp32 whatever the storage type. */
 enum { AERO_F32 = 0, AERO_BF16 = 1, AERO_F16 = 2, AERO_F8E4M3 = 3 };
 
+/* OR-ed into the dweight_dtype argument of aero_lmhead_logprob_fused: dweight += dz^T hidden instead of
+ * dweight = ..., i.e. the caller's buffer accumulates the gradient over the micro-batches of a step (the sum is
+ * formed in fp32 per entry; with a bf16 buffer the running value is rounded after every call). */
+enum { AERO_DW_ACCUMULATE = 0x100 };
+
 /* token_rollout[t] of a token row that belongs to no rollout.  Both are ignored rows; AERO_ROW_UNTOUCHED
  * additionally tells aero_grpo_loss_bwd (and its _noalloc form) not to write the row's dlogits at all, for
  * callers whose consumer of the gradient skips padding rows or who keep those rows zero themselves.  Any other
@@ -238,7 +243,7 @@ aero_status aero_grpo_loss_bwd_noalloc(
  * Forward outputs  logprob[T], lse[T] f32, entropy[T] f32 or NULL.
  * Backward part (old_logprob .. dweight; pass old_logprob == NULL for forward only):
  *   loss f32[1]; dhidden bf16 [T, H] (16-byte aligned) = dz @ weight; dweight [V, H] = dz^T @ hidden in
- *   dweight_dtype (AERO_F32 or AERO_BF16), with dz as defined for aero_grpo_loss_bwd
+ *   dweight_dtype (AERO_F32 or AERO_BF16, optionally | AERO_DW_ACCUMULATE), with dz as defined for aero_grpo_loss_bwd
  *   (entropy_coef and kl_coef / ref_logprob included: the entropy of the forward part is used,
  *   also when the `entropy` output is NULL).
  * Rows whose target or rollout index is negative take no part in the contraction (their outputs, the

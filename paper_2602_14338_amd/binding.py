@@ -14,6 +14,7 @@ import torch
 
 AERO_F32, AERO_BF16, AERO_F16, AERO_F8E4M3 = 0, 1, 2, 3
 AERO_ROW_PADDING, AERO_ROW_UNTOUCHED = -1, -2
+AERO_DW_ACCUMULATE = 0x100
 OP_GROUP_ADVANTAGE, OP_LOGPROB_FWD, OP_GRPO_LOSS_BWD, OP_LMHEAD_FUSED = 0, 1, 2, 3
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaero_hip.so")
@@ -198,7 +199,7 @@ def aero_lmhead_logprob_fused(hidden, weight, T: int, H: int, V: int, targets, l
                               eps_lo: float = 0.2, eps_hi: float = 0.2, grad_scale: float = 1.0,
                               loss=None, clip_frac=None, dhidden=None, dweight=None, workspace=None,
                               err_flag=None, entropy_coef: float = 0.0, kl_coef: float = 0.0,
-                              ref_logprob=None) -> None:
+                              ref_logprob=None, dweight_accumulate: bool = False) -> None:
     st = _lib.aero_lmhead_logprob_fused(
         _ptr(hidden, torch.bfloat16, "hidden"), _ptr(weight, torch.bfloat16, "weight"), T, H, V,
         _ptr(targets, torch.int32, "targets"), _ptr(logprob, torch.float32, "logprob"),
@@ -209,7 +210,8 @@ def aero_lmhead_logprob_fused(hidden, weight, T: int, H: int, V: int, targets, l
         _ptr(loss, torch.float32, "loss"),
         _ptr(clip_frac, torch.float32, "clip_frac"),
         _ptr(dhidden, torch.bfloat16, "dhidden"), _ptr(dweight, None, "dweight"),
-        _dtype_code(dweight) if dweight is not None else AERO_F32, _ptr(err_flag, torch.int32, "err_flag"),
+        (_dtype_code(dweight) if dweight is not None else AERO_F32) | (AERO_DW_ACCUMULATE if dweight_accumulate else 0),
+        _ptr(err_flag, torch.int32, "err_flag"),
         _ptr(workspace, None, "workspace"),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(hidden))
     _check(st, "aero_lmhead_logprob_fused")

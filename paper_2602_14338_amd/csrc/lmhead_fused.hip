@@ -828,7 +828,7 @@ template <bool OUT_BF16>
 __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
     const uint16_t* __restrict__ dzT, const uint16_t* __restrict__ hTc, int VC, int H_pad, int V, int H,
     int tile0, int n_tiles, int tiles_v, int tiles_h, int64_t T_pad, const int32_t* __restrict__ nact,
-    void* __restrict__ dW) {
+    int accumulate, void* dW) {
   extern __shared__ __align__(16) uint16_t smem[];
   int tv, th;
   if (!tile_of_block(tiles_v, tiles_h, tile0, n_tiles, tv, th)) return;
@@ -851,9 +851,18 @@ __global__ __launch_bounds__(kGemmNT, 2) void k_gemm_dw(
         const int row = m0 + acc_row(wm, mb, i, lane);
         if (row < V) {
           const int64_t o = int64_t(row) * H + col;
-          // the gradient is not read again by this call: keep it out of the caches
-          if constexpr (OUT_BF16) __builtin_nontemporal_store(f32_to_bf16(acc[mb][nb][i]), reinterpret_cast<uint16_t*>(dW) + o);
-          else __builtin_nontemporal_store(acc[mb][nb][i], reinterpret_cast<float*>(dW) + o);
+          // the gradient is not read again by this call: keep it out of the caches.  accumulate (uniform):
+          // the tile is added to what the caller's buffer holds (gradient accumulation over micro-batches)
+          float v = acc[mb][nb][i];
+          if constexpr (OUT_BF16) {
+            uint16_t* p = reinterpret_cast<uint16_t*>(dW) + o;
+            if (accumulate) v += bf16_to_f32(__builtin_nontemporal_load(p));
+            __builtin_nontemporal_store(f32_to_bf16(v), p);
+          } else {
+            float* p = reinterpret_cast<float*>(dW) + o;
+            if (accumulate) v += __builtin_nontemporal_load(p);
+            __builtin_nontemporal_store(v, p);
+          }
         }
       }
   }
@@ -919,6 +928,8 @@ extern "C" aero_status aero_lmhead_logprob_fused(
   if (T < 0 || T > 0x7fffff00LL || V < 1 || V > (1 << 24) || H < 8 || H % 8 != 0 || H > (1 << 20) || R < 0)
     return AERO_ERR_SHAPE;
   const bool bwd = old_logprob != nullptr;
+  const int accumulate = (dweight_dtype & AERO_DW_ACCUMULATE) ? 1 : 0;
+  dweight_dtype &= ~AERO_DW_ACCUMULATE;
   if (bwd && dweight_dtype != AERO_F32 && dweight_dtype != AERO_BF16) return AERO_ERR_DTYPE;
   if (!weight) return AERO_ERR_NULL;
   if (T > 0 && (!hidden || !targets || !logprob || !lse)) return AERO_ERR_NULL;
@@ -1062,10 +1073,10 @@ extern "C" aero_status aero_lmhead_logprob_fused(
       const int n = total - t0 < per ? total - t0 : per;
       if (dweight_dtype == AERO_BF16)
         hipLaunchKernelGGL((k_gemm_dw<true>), dim3(unsigned(xcd_grid(n))), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
-                           hTc, p.VC, p.H_pad, V, H, t0, n, p.tiles_v, tiles_h, p.T_pad, nact, dweight);
+                           hTc, p.VC, p.H_pad, V, H, t0, n, p.tiles_v, tiles_h, p.T_pad, nact, accumulate, dweight);
       else
         hipLaunchKernelGGL((k_gemm_dw<false>), dim3(unsigned(xcd_grid(n))), dim3(kGemmNT), kGemmLdsBytes, s, dzT,
-                           hTc, p.VC, p.H_pad, V, H, t0, n, p.tiles_v, tiles_h, p.T_pad, nact, dweight);
+                           hTc, p.VC, p.H_pad, V, H, t0, n, p.tiles_v, tiles_h, p.T_pad, nact, accumulate, dweight);
     }
   }
   if (T > 0)

@@ -61,7 +61,7 @@ def test_header_is_plain_c_and_its_constants_match_the_binding(tmp_path):
     from paper_2602_14338_amd import binding
     names = ["AERO_F32", "AERO_BF16", "AERO_F16", "AERO_F8E4M3", "AERO_ROW_PADDING", "AERO_ROW_UNTOUCHED",
              "AERO_OP_GROUP_ADVANTAGE", "AERO_OP_LOGPROB_FWD", "AERO_OP_GRPO_LOSS_BWD", "AERO_OP_LMHEAD_FUSED",
-             "AERO_NOALLOC_MAX_T"]
+             "AERO_NOALLOC_MAX_T", "AERO_DW_ACCUMULATE"]
     src = tmp_path / "consts.c"
     src.write_text('#include "aero.h"\n#include <stdio.h>\nint main(void) {\n' +
                    "".join('  printf("%s %%ld\\n", (long)%s);\n' % (n, n) for n in names) +
@@ -80,3 +80,4 @@ def test_header_is_plain_c_and_its_constants_match_the_binding(tmp_path):
                                                  binding.OP_GRPO_LOSS_BWD, binding.OP_LMHEAD_FUSED]
     assert int(got["sizeof_params"]) == ctypes.sizeof(binding._AdvParamsC)
     assert int(got["AERO_NOALLOC_MAX_T"]) == 65536
+    assert int(got["AERO_DW_ACCUMULATE"]) == binding.AERO_DW_ACCUMULATE == 0x100

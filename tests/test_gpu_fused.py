@@ -24,7 +24,8 @@ def gh():
     return gpu_helpers
 
 
-def run_fused(gh, wl, h_bits, w_bits, targets, bwd=None, dweight_dtype=torch.float32):
+def run_fused(gh, wl, h_bits, w_bits, targets, bwd=None, dweight_dtype=torch.float32, dw_into=None):
+    """dw_into: a dweight buffer to accumulate into (AERO_DW_ACCUMULATE) instead of a fresh one."""
     import paper_2602_14338_amd as aero
     from paper_2602_14338_amd import binding
     dev = gh.DEV
@@ -41,13 +42,14 @@ def run_fused(gh, wl, h_bits, w_bits, targets, bwd=None, dweight_dtype=torch.flo
     else:
         loss, clip = torch.full((1,), 7.0, device=dev), torch.full((1,), 7.0, device=dev)
         dh = torch.full((T, H), 7.0, dtype=torch.bfloat16, device=dev)
-        dw = torch.full((V, H), 7.0, dtype=dweight_dtype, device=dev)
+        dw = torch.full((V, H), 7.0, dtype=dweight_dtype, device=dev) if dw_into is None else dw_into
         aero.aero_lmhead_logprob_fused(
             hd, wd, T, H, V, gh.dev(targets), lp, ent, lse, gh.dev(bwd["old"].astype(np.float32)),
             gh.dev(wl.token_rollout), gh.dev(bwd["adv"].astype(np.float32)), gh.dev(bwd["weight"].astype(np.float32)),
             wl.R, 0.2, 0.2, bwd.get("grad_scale", 1.0), loss, clip, dh, dw, ws, err,
             entropy_coef=bwd.get("entropy_coef", 0.0), kl_coef=bwd.get("kl_coef", 0.0),
-            ref_logprob=gh.dev(bwd["ref_lp"].astype(np.float32)) if bwd.get("ref_lp") is not None else None)
+            ref_logprob=gh.dev(bwd["ref_lp"].astype(np.float32)) if bwd.get("ref_lp") is not None else None,
+            dweight_accumulate=dw_into is not None)
         out.update(loss=loss, clip_frac=clip, dhidden=dh, dweight=dw)
     torch.cuda.synchronize()
     out["err"] = int(err.item())
@@ -252,6 +254,36 @@ def test_fused_rows_outside_every_rollout(gh):
     dw = out["dweight"].float().cpu().numpy().astype(np.float64)
     assert rowwise_close(dh, ref["dhidden"]) and rowwise_close(dw, ref["dweight"])
     assert not out["dhidden"].view(torch.int16)[[5, 6, 300]].any()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fused_dweight_accumulates_over_micro_batches(gh, dtype):
+    """AERO_DW_ACCUMULATE: two micro-batches (different tokens, the same weight) through one dweight buffer give
+    the sum of their gradients.  fp32: exactly what adding the two separately computed results gives; bf16:
+    the running value is rounded after each call, checked against the checker's sum to the row tolerance."""
+    T, H, V = 520, 128, 3000
+    wl1, h1, W = make(T, H, V, sigma_w=0.3)
+    wl2, h2, _ = make(T, H, V, sigma_w=0.3, seed=11)
+
+    def inputs(wl, h):
+        ga = orc.group_advantage(wl.rewards, wl.lengths, wl.group_offsets, wl.keep_priority, AdvParams())
+        a32, w32 = ga["adv"].astype(np.float32), ga["weight"].astype(np.float32)
+        fwd = orc.lmhead_fused(h, W, wl.targets)
+        old = ai.draw_old_logprob(fwd["logprob"], wl.seed, sigma=0.3)
+        ref = orc.lmhead_fused(h, W, wl.targets, old, wl.token_rollout, a32, w32, np.float32(0.2), np.float32(0.2), 1.0)
+        return dict(old=old, adv=a32, weight=w32), ref
+    b1, ref1 = inputs(wl1, h1)
+    b2, ref2 = inputs(wl2, h2)
+    one = run_fused(gh, wl1, h1, W, wl1.targets, bwd=b1, dweight_dtype=dtype)
+    two = run_fused(gh, wl2, h2, W, wl2.targets, bwd=b2, dweight_dtype=dtype)
+    acc = one["dweight"].clone()
+    both = run_fused(gh, wl2, h2, W, wl2.targets, bwd=b2, dweight_dtype=dtype, dw_into=acc)
+    assert both["dweight"].data_ptr() == acc.data_ptr()
+    if dtype == torch.float32:
+        assert torch.equal(acc, one["dweight"] + two["dweight"])
+    want = ref1["dweight"] + ref2["dweight"]
+    assert rowwise_close(acc.float().cpu().numpy().astype(np.float64), want, frac=1e-2 if dtype == torch.float32 else 2e-2)
+    assert rowwise_close(both["dhidden"].float().cpu().numpy().astype(np.float64), ref2["dhidden"])
 
 
 def test_fused_matches_logits_path(gh):
