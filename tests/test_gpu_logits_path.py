@@ -152,7 +152,7 @@ def test_fwd_cfg1_full(gh):
 
 
 @pytest.mark.parametrize("V,ld", [(1000, 1000), (1000, 1008), (4999, 4999), (4999, 5008), (32768, 32768),
-                                  (151936, 151936), (152064, 152064), (7, 8), (1, 1), (65, 72)])
+                                  (151936, 151936), (152064, 152064), (262144, 262152), (7, 8), (1, 1), (65, 72)])
 def test_fwd_bf16_shapes(gh, V, ld):
     slots = 4 if V > 100000 else 12
     wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
@@ -391,9 +391,11 @@ def test_entropy_bonus_needs_the_entropy_array(gh):
 
 # V >= 8192 with aligned rows takes the single-pass kernel when lse is not given: 151936 and
 # 163840 (its largest row) use 20 vectors per thread, 32768 and 8200 (ragged tail) use 8;
-# 163848 is one vector too long and falls back to forward + gradient passes, as do the others.
+# 163848 is one vector too long and falls back to forward + gradient passes, as do the others
+# (262144: the largest vocabularies in use).
 @pytest.mark.parametrize("V,ld,slots", [(151936, 151936, 6), (4999, 4999, 10), (1000, 1008, 10), (32768, 32768, 10),
-                                        (8200, 8200, 10), (163840, 163848, 4), (163848, 163848, 4)])
+                                        (8200, 8200, 10), (163840, 163848, 4), (163848, 163848, 4),
+                                        (262144, 262144, 4)])
 def test_loss_bwd_cfg2_reduced(gh, V, ld, slots):
     wl = ai.make_config("cfg2", V=V, ld=ld, slots=slots, len_lo=1, len_hi=slots)
     check_loss_bwd(gh, wl, dict())
