@@ -4,7 +4,8 @@ forms the logits as a float64 product and then applies the logits-path definitio
 
 Tolerances: log-prob / entropy / lse 2e-3 absolute; loss 1e-4 relative (plus an fp32 rounding floor only where the terms cancel, see gpu_helpers.loss_bound); gradients are checked
 scale-free, per row, against 1e-2 of the largest reference entry of that row (the operands of
-the two gradient contractions are rounded to bf16, dhidden is stored in bf16)."""
+the two gradient contractions are rounded to bf16, dhidden is stored in bf16); a dweight
+requested in bf16 is allowed the rounding of its own stored entries, 2^-8 relative, on top."""
 import numpy as np
 import pytest
 import torch
@@ -63,9 +64,12 @@ def make(T, H, V, Q=6, sigma_w=None, name="cfg4", seed=None, len_hi=None):
     return wl, wl.hidden_rows(0, T), wl.weight_rows(0, V)
 
 
-def rowwise_close(got, want, frac=1e-2):
+def rowwise_close(got, want, frac=1e-2, stored_rounding=0.0):
+    """stored_rounding: relative rounding of the stored entry itself, allowed on top (2^-8 for a dweight the
+    caller asks for in bf16; over a vocabulary of 2^18 rows the tail of the operand-rounding noise comes within
+    a tenth of the row bound, and the output's own rounding is a separate, known quantity)."""
     scale = np.abs(want).max(axis=1, keepdims=True)
-    return (np.abs(got - want) <= frac * scale + 1e-30).all()
+    return (np.abs(got - want) <= frac * scale + stored_rounding * np.abs(want) + 1e-30).all()
 
 
 # (300, 2112, 1000): 33 K slices, the contraction loop's L2 warm-up (from 32 slices on) is active
@@ -114,16 +118,17 @@ def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, 
     dw = out["dweight"].float().cpu().numpy().astype(np.float64)
     assert np.isfinite(dh).all() and np.isfinite(dw).all()
     assert rowwise_close(dh, ref["dhidden"])
-    assert rowwise_close(dw, ref["dweight"])
+    assert rowwise_close(dw, ref["dweight"], stored_rounding=2.0 ** -8 if dweight_dtype == torch.bfloat16 else 0.0)
     dead = (ref["g"] == 0) & (ref["e"] == 0)
     assert not out["dhidden"].view(torch.int16)[torch.from_numpy(dead).to(gh.DEV)].any()   # +0 rows
     return ref, out
 
 
 # the last two reach 32 K slices in the recompute (H = 2112) and in the dweight contraction (> 2048 tokens
-# with gradient), where the loop warms L2 ahead of its operand requests
+# with gradient), where the loop warms L2 ahead of its operand requests; the last one has 1024 vocabulary tiles
 @pytest.mark.parametrize("T,H,V", [(256, 64, 256), (300, 64, 1000), (17, 72, 77), (700, 512, 5000),
-                                   (512, 1536, 3000), (1100, 256, 4096), (300, 2112, 1000), (4500, 64, 600)])
+                                   (512, 1536, 3000), (1100, 256, 4096), (300, 2112, 1000), (4500, 64, 600),
+                                   (300, 64, 262144)])
 def test_fused_backward(gh, T, H, V):
     wl, h, W = make(T, H, V, sigma_w=2.0 / np.sqrt(H))
     ref, _ = check_bwd(gh, wl, h, W, dict())
