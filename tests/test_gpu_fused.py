@@ -125,10 +125,10 @@ def check_bwd(gh, wl, h, W, params, sigma_old=0.3, dweight_dtype=torch.float32, 
 
 
 # the last two reach 32 K slices in the recompute (H = 2112) and in the dweight contraction (> 2048 tokens
-# with gradient), where the loop warms L2 ahead of its operand requests; the last one has 1024 vocabulary tiles
+# with gradient), where the loop warms L2 ahead of its operand requests; then 1024 vocabulary tiles, and a hidden size of 8192
 @pytest.mark.parametrize("T,H,V", [(256, 64, 256), (300, 64, 1000), (17, 72, 77), (700, 512, 5000),
                                    (512, 1536, 3000), (1100, 256, 4096), (300, 2112, 1000), (4500, 64, 600),
-                                   (300, 64, 262144)])
+                                   (300, 64, 262144), (130, 8192, 700)])
 def test_fused_backward(gh, T, H, V):
     wl, h, W = make(T, H, V, sigma_w=2.0 / np.sqrt(H))
     ref, _ = check_bwd(gh, wl, h, W, dict())
