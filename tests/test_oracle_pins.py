@@ -619,6 +619,44 @@ def test_zero_variance_groups_cost_nothing():
     assert out["dlogits"][~dead].any()
 
 
+def test_row_shift_and_vocabulary_relabelling_leave_the_step_unchanged():
+    """A softmax policy (App. C) does not see a constant added to a row of logits, and renaming the
+    vocabulary entries only renames the gradient's columns: log-prob, entropy, loss and clip fraction
+    stay, lse moves by the constant, dlogits is permuted.  All optional terms on."""
+    rng = np.random.default_rng(31)
+    T, V, R = 40, 23, 6
+    z = rng.normal(0, 3, size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    tr = rng.integers(-1, R, size=T).astype(np.int32)
+    adv = rng.normal(size=R)
+    adv[2] = 0.0
+    w = rng.random(R) * 0.01
+    base = [orc.logprob_row(z[t], y[t]) for t in range(T)]
+    old = np.array([b[0] for b in base]) + rng.normal(0, 0.3, size=T)
+    ref_lp = old + rng.normal(0, 0.2, size=T)
+    kw = dict(grad_scale=3.0, entropy_coef=0.02, kl_coef=0.04, ref_logprob=ref_lp)
+    out = orc.grpo_loss_bwd(None, "f64", V, y, old, tr, adv, w, 0.2, 0.2, z64=z, **kw)
+    assert 0.0 < out["clip_frac"] < 1.0 and out["dlogits"].any()
+
+    shift = rng.normal(0, 50, size=(T, 1))
+    for t in range(T):
+        lp, ent, lse = orc.logprob_row(z[t] + shift[t], y[t])
+        assert abs(lp - base[t][0]) < 1e-12 and abs(ent - base[t][1]) < 1e-12
+        assert abs(lse - base[t][2] - shift[t, 0]) < 1e-12
+    shifted = orc.grpo_loss_bwd(None, "f64", V, y, old, tr, adv, w, 0.2, 0.2, z64=z + shift, **kw)
+    assert abs(shifted["loss"] - out["loss"]) < 1e-14 and shifted["clip_frac"] == out["clip_frac"]
+    assert np.abs(shifted["dlogits"] - out["dlogits"]).max() < 1e-13
+
+    perm = rng.permutation(V)                   # new column j holds old column perm[j]
+    inv = np.argsort(perm)
+    renamed = orc.grpo_loss_bwd(None, "f64", V, inv[y].astype(np.int32), old, tr, adv, w, 0.2, 0.2,
+                                z64=z[:, perm], **kw)
+    assert abs(renamed["loss"] - out["loss"]) < 1e-14 and renamed["clip_frac"] == out["clip_frac"]
+    assert np.abs(renamed["dlogits"] - out["dlogits"][:, perm]).max() < 1e-15
+    # and the gradient rows of a softmax sum to zero over the vocabulary, with or without the extra terms
+    assert np.abs(out["dlogits"].sum(axis=1)).max() < 1e-15
+
+
 # ------------------------------------------------------------------ fused LM head
 
 def test_fused_matches_autograd_through_the_matmul():
